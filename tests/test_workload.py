@@ -1,0 +1,48 @@
+"""Checks of the synthetic input generator against the paper's token arithmetic
+(Sec. 3.1; Table A-1 caption) and the benchmark shapes."""
+import numpy as np
+
+from workload import CONFIGS, bf16_bits_to_f32, generate_head, round_to_bf16_bits
+
+
+def test_token_arithmetic():
+    assert 518 // 14 == 37 and 392 // 14 == 28
+    assert CONFIGS[1].tokens_per_frame == 1 + 4 + 37 * 37 == 1374
+    assert CONFIGS[5].tokens_per_frame == 1 + 4 + 28 * 37 == 1041
+    assert [CONFIGS[i].n_tokens for i in range(1, 6)] == [2748, 10992, 43968, 137400, 312300]
+    assert [CONFIGS[i].n_blocks for i in range(1, 6)] == [43, 172, 344, 1074, 2440]
+    # Sec. 4.1: ten frames at 294x518 -> (10*294*518/14^2)^2 = 7770^2 = 6.04e7 entries; the
+    # printed 1.2e8 matches that count in bytes at half precision (">100MB"), not in entries.
+    assert (10 * 294 * 518) // 14 ** 2 == 7770
+    assert abs(7770 ** 2 * 2 / 1.2e8 - 1) < 0.03
+
+
+def test_bf16_rounding_is_nearest_even():
+    import torch
+    x = np.random.default_rng(0).standard_normal(10000).astype(np.float32)
+    x[:4] = [1.0, 1.00390625, 1.01171875, -3.0e-3]  # exact, tie-to-even down, tie-to-even up
+    ours = bf16_bits_to_f32(round_to_bf16_bits(x))
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    np.testing.assert_array_equal(ours, ref)
+
+
+def test_generator_is_seeded_and_structured():
+    cfg = CONFIGS[2]
+    q, k, v = generate_head(cfg, 3, frames=2)
+    q2, _, _ = generate_head(cfg, 3, frames=2)
+    np.testing.assert_array_equal(q, q2)
+    q3, _, _ = generate_head(cfg, 4, frames=2)
+    assert not np.array_equal(q, q3)
+    assert q.shape == (2 * 1374, 64) and q.dtype == np.float32
+    np.testing.assert_array_equal(q, bf16_bits_to_f32(round_to_bf16_bits(q)))  # already bf16 values
+    # patch tokens: |4z + 0.5 n|^2 ~ 16 + 16; special tokens ~ 64
+    n2 = (q.astype(np.float64) ** 2).sum(1).reshape(2, 1374)
+    assert abs(n2[:, 5:].mean() - 32) < 1.5 and abs(n2[:, :5].mean() - 64) < 25
+    assert abs(v.std() - 1) < 0.02
+
+
+def test_partial_visibility_config_runs_small():
+    cfg = CONFIGS[3]
+    q, k, v = generate_head(cfg, 0, frames=3)
+    assert q.shape == (3 * 1374, 64)
+    assert np.isfinite(q).all() and np.isfinite(k).all()
