@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-sparse global-attention layer on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch that is already resident in
+HBM: block pooling of Q and K, block scoring + selection, V repack and block-sparse attention.
+The default workload is the headline shape: 100 frames x 1374 tokens = 137,400 tokens, 16 heads,
+head dim 64, bf16, block 128, tau = 0.9.  The dense kernel is timed on the same inputs.
+
+Prints ONE JSON line (see the design doc for the fields).  `value` is the kept-block throughput of the
+whole layer: FLOPs of the kept (query block, key block) pairs, counting valid tokens only,
+divided by the layer time.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0
+
+
+def kept_flops(kv_idx, kv_cnt, n_tokens: int, block: int) -> float:
+    """4 * n_I * n_J * 64 summed over kept pairs, with n_I, n_J the valid tokens of each block."""
+    import torch
+    H, nb, _ = kv_idx.shape
+    tail = n_tokens - (nb - 1) * block
+    cnt = kv_cnt.to(torch.int64)
+    ar = torch.arange(kv_idx.shape[-1], device=kv_idx.device)[None, None, :]
+    has_last = ((kv_idx == nb - 1) & (ar < cnt[..., None])).any(-1)
+    keys = cnt * block - has_last.to(torch.int64) * (block - tail)          # valid keys per row
+    rows = torch.full((nb,), block, device=kv_idx.device, dtype=torch.int64)
+    rows[-1] = tail
+    return float((keys * rows[None, :]).sum().item()) * 4.0 * 64.0
+
+
+def cpu_baseline(cfg, tau: float, budget_s: float = 20.0):
+    """Times the fp64 numpy oracle on a bounded sample of the same workload: one head's mask
+    prediction over the full sequence, then masked attention for query blocks of that head until
+    the time budget is used.  Returns kept-block TFLOP/s of the sampled work."""
+    import numpy as np
+    from oracle import bsga_oracle as O
+    from workload import generate_head
+
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    q, k, v = generate_head(cfg, 0)
+    q, k, v = q[None], k[None], v[None]
+    b, N = cfg.block, cfg.n_tokens
+    t0 = time.perf_counter()
+    mask = O.predict_mask(q, k, b, tau, 1.0)
+    t_mask = time.perf_counter() - t0
+    nb = mask.shape[-1]
+    tail = N - (nb - 1) * b
+    flops = 0.0
+    done = 0
+    t1 = time.perf_counter()
+    order = [0, nb - 1] + list(range(1, nb - 1))
+    for I in order:
+        O.sparse_attention(q, k, v, mask, b, q_blocks=[I])
+        n_i = tail if I == nb - 1 else b
+        keys = int(mask[0, I].sum()) * b - (b - tail if mask[0, I, nb - 1] else 0)
+        flops += 4.0 * 64.0 * n_i * keys
+        done += 1
+        if time.perf_counter() - t1 > budget_s:
+            break
+    t_attn = time.perf_counter() - t1
+    # the mask prediction covers all nb rows of the head; charge the sampled rows their share
+    t_total = t_attn + t_mask * done / nb
+    return {
+        "value": flops / t_total / 1e12,
+        "unit": "TFLOP/s",
+        "cores": int(threads),
+        "kind": "oracle",
+        "sample": f"head 0: mask prediction for all {nb} query blocks ({t_mask:.2f} s, charged pro rata) + masked "
+                  f"attention of {done} query blocks over the full key range ({t_attn:.1f} s), fp64 numpy",
+        "layer_seconds_extrapolated": t_total / done * nb * cfg.heads,
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--cfg", type=int, default=4, help="workload id (1-5); 4 is the headline 100-frame shape")
+    ap.add_argument("--tau", type=float, default=0.9)
+    ap.add_argument("--rho", type=float, default=1.0)
+    ap.add_argument("--dense-steps", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=20.0)
+    ap.add_argument("--sweep", action="store_true", help="also print per-(tau, rho) rows to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding or collectives are implemented); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2509_07120_amd as B
+    from workload import CONFIGS, generate
+
+    cfg = CONFIGS[args.cfg]
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    t0 = time.time()
+    q, k, v = generate(cfg)
+    tq, tk, tv = (torch.from_numpy(x).to(dt).cuda() for x in (q, k, v))
+    del q, k, v
+    print(f"[bench] generated cfg {cfg.cfg_id} ({cfg.name}) in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
+    H, N, d = tq.shape
+    b = cfg.block
+    ws_bytes = B.bsga_attn_workspace_bytes(dt, H, N, d)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(tq)
+
+    def layer(tau, rho, events=None):
+        if events:
+            events[0].record()
+        qp, kp = B.bsga_pool_qk(tq, tk, b)
+        if events:
+            events[1].record()
+        bits, idx, cnt = B.bsga_select_blocks(qp, kp, tau, rho, want_bits=False)
+        if events:
+            events[2].record()
+        B.bsga_sparse_attn(tq, tk, tv, b, idx, cnt, out=out, workspace=ws)
+        if events:
+            events[3].record()
+        return idx, cnt
+
+    def run(tau, rho, steps, warmup):
+        for _ in range(warmup):
+            idx, cnt = layer(tau, rho)
+        torch.cuda.synchronize()
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+        t0 = time.perf_counter()
+        for s in range(steps):
+            idx, cnt = layer(tau, rho, evs[s])
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        stage = [sum(e[i].elapsed_time(e[i + 1]) for e in evs) / steps for i in range(3)]
+        flops = kept_flops(idx, cnt, N, b)
+        kept_frac = float(cnt.to(torch.float64).sum().item()) / (H * cfg.n_blocks * cfg.n_blocks)
+        return wall_ms, stage, flops, kept_frac
+
+    wall_ms, stage, flops, kept_frac = run(args.tau, args.rho, args.steps, args.warmup)
+
+    # dense baseline on the same inputs
+    dense_ms = None
+    if args.dense_steps > 0:
+        B.bsga_dense_attn(tq, tk, tv, out=out, workspace=ws)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.dense_steps):
+            B.bsga_dense_attn(tq, tk, tv, out=out, workspace=ws)
+        e1.record()
+        torch.cuda.synchronize()
+        dense_ms = e0.elapsed_time(e1) / args.dense_steps
+    dense_flops = 4.0 * H * float(N) * float(N) * d
+
+    if args.sweep:
+        for tau, rho in [(0.8, 1.0), (0.9, 1.0), (0.95, 1.0), (0.0, 0.5), (0.0, 0.75), (0.0, 0.9)]:
+            w, st, fl, kf = run(tau, rho, max(2, args.steps // 2), 1)
+            print(f"[sweep] tau={tau} rho={rho} kept={kf:.4f} layer_ms={w:.3f} pool={st[0]:.3f} select={st[1]:.3f} "
+                  f"attn={st[2]:.3f} kept_TFLOPs={fl / (w * 1e-3) / 1e12:.1f} "
+                  f"speedup_vs_dense={(dense_ms / w) if dense_ms else float('nan'):.3f}", file=sys.stderr, flush=True)
+
+    attn_ms = stage[2]
+    achieved = flops / (attn_ms * 1e-3) / 1e12
+    value = flops / (wall_ms * 1e-3) / 1e12
+    rec = {
+        "metric": "global-attn layer ms + kept-block TFLOP/s (% bf16 peak) at 100 frames vs dense",
+        "value": value,
+        "unit": "TFLOP/s (kept-block FLOPs / whole layer time)",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall_ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"cfg{cfg.cfg_id}: {cfg.frames} frames x {cfg.tokens_per_frame} tokens = {N} tokens, "
+                               f"{H} heads, d={d}, {cfg.dtype}, block {b}, tau={args.tau}, rho={args.rho}"},
+        "layer_ms": wall_ms,
+        "stage_ms": {"pool": stage[0], "select": stage[1], "attention_incl_v_repack": stage[2]},
+        "kept_fraction": kept_frac,
+        "pct_of_bf16_peak": 100.0 * value / PEAK_BF16_TFLOPS,
+        "dense_ms": dense_ms,
+        "dense_tflops": (dense_flops / (dense_ms * 1e-3) / 1e12) if dense_ms else None,
+        "speedup_vs_dense": (dense_ms / wall_ms) if dense_ms else None,
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "kernel": "attn_bf16_kernel<128> (block-sparse attention incl. V repack)"},
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(cfg, args.tau, args.cpu_budget)
+    print(json.dumps(rec), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,125 @@
+/*
+ * bsga -- block-sparse global attention for MI355X (gfx950).  C ABI.
+ *
+ * The library implements the training-free block-sparse replacement for dense
+ * global attention in multi-view geometry transformers:
+ *   1. pool Q and K per block of b tokens                (Sec. 4.1, "Predicting Block Masks")
+ *   2. block scores S = P^b(Q) P^b(K)^T, row softmax      (same paragraph)
+ *   3. CDF-threshold (tau) + top-k floor (rho) selection  (Sec. 4.1, "Selecting Blocks")
+ *   4. softmax attention over the kept key blocks only    (Sec. 4.1, Eq. (2))
+ * plus the dense baseline of Eq. (1).
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers unless marked "host".  The caller owns
+ *     every buffer; the library allocates, frees and copies nothing, and only enqueues
+ *     work on `stream` (a hipStream_t passed as void*; NULL = the null stream).  Calls
+ *     return after enqueueing; they do not synchronise.
+ *   - Tensors are contiguous row-major; Q, K, V, O are [heads, n_tokens, head_dim]
+ *     (a batch dimension is folded into heads).  Pointers must be 16-byte aligned.
+ *   - head_dim must be 64.  block must be 64 or 128.  dtype: BSGA_BF16 or BSGA_FP32
+ *     (the fp32 path is a correctness path, not a tuned one).
+ *   - Blocks: block I covers tokens I*block .. min((I+1)*block, n_tokens)-1;
+ *     nb = ceil(n_tokens / block).  The last block may be ragged.
+ *   - Return value: BSGA_OK or an error code; bsga_last_error() gives a message
+ *     (thread-local).  Arguments are validated before anything is launched, so
+ *     argument errors can be observed without a GPU.
+ */
+#ifndef BSGA_H
+#define BSGA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BSGA_OK 0
+#define BSGA_ERR_INVALID_ARG 1
+#define BSGA_ERR_UNSUPPORTED 2
+#define BSGA_ERR_WORKSPACE 3
+#define BSGA_ERR_HIP 4
+
+#define BSGA_BF16 0
+#define BSGA_FP32 1
+
+/* ABI version of this header (bumped on incompatible change). */
+int bsga_version(void);
+
+/* Message for the last error returned on this thread ("" if none). Host pointer, library-owned. */
+const char* bsga_last_error(void);
+
+/*
+ * Block average pooling of Q and K  (Sec. 4.1, "Predicting Block Masks": P^b(Q), P^b(K)).
+ *   q, k          [heads, n_tokens, 64], dtype as given
+ *   q_pool,k_pool [heads, nb, 64] float64 out; block I is the mean over its valid tokens
+ *                 (the ragged last block divides by its own token count).
+ * Sums are accumulated in float64, so for bf16 inputs the block sums are exact.
+ * Either of (q, q_pool) or (k, k_pool) may be NULL together to pool only one tensor.
+ */
+int bsga_pool_qk(const void* q, const void* k, int dtype, int heads, int64_t n_tokens, int head_dim,
+                 int block, double* q_pool, double* k_pool, void* stream);
+
+/*
+ * Block scores, block softmax and block selection  (Sec. 4.1, "Predicting Block Masks" and
+ * "Selecting Blocks").  For every head h and query block I:
+ *   logits[J] = score_scale * <q_pool[h,I], k_pool[h,J]>,  p = softmax_J(logits)      (float64)
+ *   rank key blocks by descending p, equal p by ascending J;
+ *   n_cdf = length of the shortest ranked prefix whose summed p is >= tau
+ *           (all nb_k blocks if tau >= 1 or the sum never gets there);
+ *   k = floor(nb_k * (1 - rho)) evaluated in float64;  n = min(nb_k, max(n_cdf, k, 1));
+ *   the first n ranked blocks are kept.
+ * Then, if given (Sec. 4.2, special tokens stay dense): force_q[I] != 0 keeps the whole row I,
+ * force_k[J] != 0 keeps column J in every row.
+ *   q_pool   [heads, nb_q, 64] float64      k_pool [heads, nb_k, 64] float64
+ *   force_q  nullable [nb_q] uint8          force_k nullable [nb_k] uint8
+ * Outputs (each nullable):
+ *   mask_bits [heads, nb_q, ceil(nb_k/32)] uint32, bit (J%32) of word J/32 set iff (I,J) kept;
+ *   kv_idx    [heads, nb_q, idx_stride] int32, the kept J in ascending order; entries past the
+ *             count are left untouched;  idx_stride >= nb_k;
+ *   kv_cnt    [heads, nb_q] int32, number of kept blocks.
+ * Limits: 1 <= nb_k <= 4096.  score_scale must be finite; 0 <= tau; 0 <= rho <= 1.
+ */
+int bsga_select_blocks(const double* q_pool, const double* k_pool, int heads, int nb_q, int nb_k,
+                       int head_dim, double score_scale, double tau, double rho,
+                       const uint8_t* force_q, const uint8_t* force_k, uint32_t* mask_bits,
+                       int32_t* kv_idx, int32_t* kv_cnt, int idx_stride, void* stream);
+
+/*
+ * Bytes of device workspace bsga_sparse_attn / bsga_dense_attn need for this shape
+ * (a repacked copy of V for the bf16 path; 0 for fp32).  Returns 0 on invalid arguments.
+ */
+size_t bsga_attn_workspace_bytes(int dtype, int heads, int64_t n_tokens, int head_dim);
+
+/*
+ * Block-sparse attention  (Sec. 4.1, Eq. (2), with masked entries excluded from the softmax).
+ * For token i in query block I of head h:
+ *   o_i = sum_j softmax_j(softmax_scale * <q_i, k_j>) v_j   over keys j < n_tokens that lie in
+ *   the key blocks kv_idx[h, I, 0 .. kv_cnt[h,I]-1].
+ *   q, k, v  [heads, n_tokens, 64], dtype as given;  out same shape and dtype
+ *   kv_idx   [heads, nb, idx_stride] int32, each row's kept key blocks: distinct, in [0, nb);
+ *   kv_cnt   [heads, nb] int32, 1 <= count <= nb (a row with count 0 yields zeros, lse = -inf)
+ *   lse      nullable [heads, n_tokens] float32: natural-log sum-exp of each row's kept logits
+ *   workspace, workspace_bytes: device scratch of at least bsga_attn_workspace_bytes(...);
+ *            contents are overwritten; calls sharing one workspace must be stream-ordered.
+ * bf16: products on bf16 MFMA with fp32 accumulation, fp32 online softmax.  softmax_scale > 0.
+ * The index lists are trusted to be in range (they come from bsga_select_blocks); block
+ * indices are clamped to [0, nb) before use so a corrupt list cannot read out of bounds.
+ */
+int bsga_sparse_attn(const void* q, const void* k, const void* v, int dtype, int heads,
+                     int64_t n_tokens, int head_dim, int block, float softmax_scale,
+                     const int32_t* kv_idx, const int32_t* kv_cnt, int idx_stride, void* out,
+                     float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Dense attention baseline  (Sec. 4.1, Eq. (1)): softmax(softmax_scale * Q K^T) V per head.
+ * Same tensors, workspace and numerics as bsga_sparse_attn, every key visible.
+ */
+int bsga_dense_attn(const void* q, const void* k, const void* v, int dtype, int heads,
+                    int64_t n_tokens, int head_dim, float softmax_scale, void* out, float* lse,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BSGA_H */

@@ -1,0 +1,206 @@
+"""ctypes binding of libbsga.so: argument marshalling only.
+
+Every function here forwards to the C-ABI entry point of the same name with
+device pointers taken from torch tensors and the current torch HIP stream.
+Outputs and workspaces are torch tensors (torch is the device allocator and
+stream provider, nothing else); all arithmetic happens in the HIP kernels.
+There is no fallback path: if the library is missing or a call fails, an
+exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libbsga.so")
+
+BSGA_OK = 0
+BSGA_ERR_INVALID_ARG = 1
+BSGA_ERR_UNSUPPORTED = 2
+BSGA_ERR_WORKSPACE = 3
+BSGA_ERR_HIP = 4
+BSGA_BF16 = 0
+BSGA_FP32 = 1
+
+EXPORTED_SYMBOLS = (
+    "bsga_version",
+    "bsga_last_error",
+    "bsga_pool_qk",
+    "bsga_select_blocks",
+    "bsga_attn_workspace_bytes",
+    "bsga_sparse_attn",
+    "bsga_dense_attn",
+)
+
+
+class BsgaError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"bsga error {code}: {message}")
+        self.code = code
+        self.message = message
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
+            "or `python paper_2509_07120_amd/build.py` first (there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    c_void_p, c_int, c_int64, c_double, c_float, c_size_t = (
+        ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_double, ctypes.c_float, ctypes.c_size_t)
+    lib.bsga_version.restype = c_int
+    lib.bsga_version.argtypes = []
+    lib.bsga_last_error.restype = ctypes.c_char_p
+    lib.bsga_last_error.argtypes = []
+    lib.bsga_pool_qk.restype = c_int
+    lib.bsga_pool_qk.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int64, c_int, c_int, c_void_p, c_void_p, c_void_p]
+    lib.bsga_select_blocks.restype = c_int
+    lib.bsga_select_blocks.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_double, c_double, c_double,
+                                       c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p]
+    lib.bsga_attn_workspace_bytes.restype = c_size_t
+    lib.bsga_attn_workspace_bytes.argtypes = [c_int, c_int, c_int64, c_int]
+    lib.bsga_sparse_attn.restype = c_int
+    lib.bsga_sparse_attn.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int64, c_int, c_int, c_float,
+                                     c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.bsga_dense_attn.restype = c_int
+    lib.bsga_dense_attn.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int64, c_int, c_float,
+                                    c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    return lib
+
+
+lib = _load()
+
+
+def _check(rc: int) -> None:
+    if rc != BSGA_OK:
+        raise BsgaError(rc, lib.bsga_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(t: torch.Tensor) -> int:
+    return torch.cuda.current_stream(t.device).cuda_stream
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return BSGA_BF16
+    if t.dtype == torch.float32:
+        return BSGA_FP32
+    raise TypeError(f"unsupported dtype {t.dtype}: bsga takes bfloat16 or float32")
+
+
+def _require(t: torch.Tensor, name: str, dtype=None) -> None:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+
+
+def num_blocks(n_tokens: int, block: int) -> int:
+    return (n_tokens + block - 1) // block
+
+
+def bsga_pool_qk(q: torch.Tensor, k: torch.Tensor, block: int) -> Tuple[torch.Tensor, torch.Tensor]:
+    """q, k [H, N, 64] -> (q_pool, k_pool) [H, ceil(N/block), 64] float64."""
+    _require(q, "q"); _require(k, "k", q.dtype)
+    if q.shape != k.shape or q.dim() != 3:
+        raise ValueError("q and k must both be [heads, n_tokens, head_dim]")
+    H, N, d = q.shape
+    nb = num_blocks(N, block)
+    q_pool = torch.empty((H, nb, d), dtype=torch.float64, device=q.device)
+    k_pool = torch.empty_like(q_pool)
+    _check(lib.bsga_pool_qk(_ptr(q), _ptr(k), _dtype_code(q), H, N, d, block, _ptr(q_pool), _ptr(k_pool), _stream(q)))
+    return q_pool, k_pool
+
+
+def bsga_select_blocks(q_pool: torch.Tensor, k_pool: torch.Tensor, tau: float, rho: float = 1.0,
+                       score_scale: Optional[float] = None, force_q: Optional[torch.Tensor] = None,
+                       force_k: Optional[torch.Tensor] = None, want_bits: bool = True):
+    """Pooled Q/K -> (mask_bits [H,nbq,ceil(nbk/32)] uint32-as-int32, kv_idx [H,nbq,nbk] int32, kv_cnt [H,nbq] int32)."""
+    _require(q_pool, "q_pool", torch.float64); _require(k_pool, "k_pool", torch.float64)
+    H, nbq, d = q_pool.shape
+    nbk = k_pool.shape[1]
+    if score_scale is None:
+        score_scale = 1.0 / math.sqrt(d)
+    dev = q_pool.device
+    words = (nbk + 31) // 32
+    mask_bits = torch.zeros((H, nbq, words), dtype=torch.int32, device=dev) if want_bits else None
+    kv_idx = torch.empty((H, nbq, nbk), dtype=torch.int32, device=dev)
+    kv_cnt = torch.empty((H, nbq), dtype=torch.int32, device=dev)
+    if force_q is not None:
+        _require(force_q, "force_q", torch.uint8)
+    if force_k is not None:
+        _require(force_k, "force_k", torch.uint8)
+    _check(lib.bsga_select_blocks(_ptr(q_pool), _ptr(k_pool), H, nbq, nbk, d, float(score_scale), float(tau),
+                                  float(rho), _ptr(force_q), _ptr(force_k), _ptr(mask_bits), _ptr(kv_idx),
+                                  _ptr(kv_cnt), nbk, _stream(q_pool)))
+    return mask_bits, kv_idx, kv_cnt
+
+
+def bsga_attn_workspace_bytes(dtype: torch.dtype, heads: int, n_tokens: int, head_dim: int = 64) -> int:
+    code = BSGA_BF16 if dtype == torch.bfloat16 else BSGA_FP32
+    return int(lib.bsga_attn_workspace_bytes(code, heads, n_tokens, head_dim))
+
+
+def _workspace(q: torch.Tensor, workspace: Optional[torch.Tensor]) -> Tuple[Optional[torch.Tensor], int]:
+    H, N, d = q.shape
+    need = bsga_attn_workspace_bytes(q.dtype, H, N, d)
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    return workspace, nbytes
+
+
+def bsga_sparse_attn(q, k, v, block: int, kv_idx: torch.Tensor, kv_cnt: torch.Tensor,
+                     softmax_scale: Optional[float] = None, return_lse: bool = False,
+                     out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+    """Attention of each query block over its kept key blocks; returns O (and lse)."""
+    _require(q, "q"); _require(k, "k", q.dtype); _require(v, "v", q.dtype)
+    _require(kv_idx, "kv_idx", torch.int32); _require(kv_cnt, "kv_cnt", torch.int32)
+    H, N, d = q.shape
+    if softmax_scale is None:
+        softmax_scale = 1.0 / math.sqrt(d)
+    if out is None:
+        out = torch.empty_like(q)
+    lse = torch.empty((H, N), dtype=torch.float32, device=q.device) if return_lse else None
+    workspace, ws_bytes = _workspace(q, workspace)
+    _check(lib.bsga_sparse_attn(_ptr(q), _ptr(k), _ptr(v), _dtype_code(q), H, N, d, block, float(softmax_scale),
+                                _ptr(kv_idx), _ptr(kv_cnt), kv_idx.shape[-1], _ptr(out), _ptr(lse),
+                                _ptr(workspace), ws_bytes, _stream(q)))
+    return (out, lse) if return_lse else out
+
+
+def bsga_dense_attn(q, k, v, softmax_scale: Optional[float] = None, return_lse: bool = False,
+                    out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+    """Dense softmax attention baseline; returns O (and lse)."""
+    _require(q, "q"); _require(k, "k", q.dtype); _require(v, "v", q.dtype)
+    H, N, d = q.shape
+    if softmax_scale is None:
+        softmax_scale = 1.0 / math.sqrt(d)
+    if out is None:
+        out = torch.empty_like(q)
+    lse = torch.empty((H, N), dtype=torch.float32, device=q.device) if return_lse else None
+    workspace, ws_bytes = _workspace(q, workspace)
+    _check(lib.bsga_dense_attn(_ptr(q), _ptr(k), _ptr(v), _dtype_code(q), H, N, d, float(softmax_scale),
+                               _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes, _stream(q)))
+    return (out, lse) if return_lse else out
+
+
+def sparse_global_attention(q, k, v, block: int, tau: float, rho: float = 1.0,
+                            score_scale: Optional[float] = None, softmax_scale: Optional[float] = None,
+                            workspace: Optional[torch.Tensor] = None):
+    """The whole layer: pool -> select -> block-sparse attention.  Returns (O, kv_idx, kv_cnt, mask_bits)."""
+    q_pool, k_pool = bsga_pool_qk(q, k, block)
+    mask_bits, kv_idx, kv_cnt = bsga_select_blocks(q_pool, k_pool, tau, rho, score_scale)
+    out = bsga_sparse_attn(q, k, v, block, kv_idx, kv_cnt, softmax_scale, workspace=workspace)
+    return out, kv_idx, kv_cnt, mask_bits

@@ -1,0 +1,167 @@
+// C-ABI entry points of libbsga: argument validation and dispatch to the kernel launchers.
+// Validation runs before any HIP call, so argument errors are reported on machines without a GPU.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "bsga_internal.h"
+
+namespace bsga {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+void clear_error() { g_err[0] = '\0'; }
+
+int check_hip(hipError_t e, const char* what) {
+  if (e == hipSuccess) return BSGA_OK;
+  return fail(BSGA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static int check_shape(const char* fn, int dtype, int heads, int64_t n_tokens, int head_dim) {
+  if (dtype != BSGA_BF16 && dtype != BSGA_FP32)
+    return fail(BSGA_ERR_INVALID_ARG, "%s: dtype must be BSGA_BF16 (0) or BSGA_FP32 (1), got %d", fn, dtype);
+  if (heads < 1 || heads > 65535)
+    return fail(BSGA_ERR_INVALID_ARG, "%s: heads must be in [1, 65535], got %d", fn, heads);
+  if (n_tokens < 1) return fail(BSGA_ERR_INVALID_ARG, "%s: n_tokens must be >= 1, got %lld", fn, (long long)n_tokens);
+  if (n_tokens > (int64_t(1) << 24))
+    return fail(BSGA_ERR_UNSUPPORTED, "%s: n_tokens above 2^24 is not supported, got %lld", fn, (long long)n_tokens);
+  if (head_dim != 64) return fail(BSGA_ERR_UNSUPPORTED, "%s: head_dim must be 64, got %d", fn, head_dim);
+  return BSGA_OK;
+}
+
+static int check_block(const char* fn, int block) {
+  if (block != 64 && block != 128)
+    return fail(BSGA_ERR_UNSUPPORTED, "%s: block must be 64 or 128, got %d", fn, block);
+  return BSGA_OK;
+}
+
+static size_t attn_workspace(int dtype, int heads, int64_t n_tokens) {
+  if (dtype != BSGA_BF16) return 0;
+  // repacked V: [heads, ceil(N/128)*128, 64] bf16
+  return size_t(heads) * size_t(ceil_div(n_tokens, 128) * 128) * 64 * 2;
+}
+
+static int attn_common(const char* fn, const void* q, const void* k, const void* v, int dtype, int heads,
+                       int64_t n_tokens, int head_dim, int block, float softmax_scale,
+                       const int32_t* kv_idx, const int32_t* kv_cnt, int idx_stride, void* out, float* lse,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  if (int rc = check_shape(fn, dtype, heads, n_tokens, head_dim)) return rc;
+  if (int rc = check_block(fn, block)) return rc;
+  if (!q || !k || !v || !out) return fail(BSGA_ERR_INVALID_ARG, "%s: q, k, v and out must be non-null", fn);
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
+    return fail(BSGA_ERR_INVALID_ARG, "%s: q, k, v and out must be 16-byte aligned", fn);
+  if (!(softmax_scale > 0.0f) || !isfinite(softmax_scale))
+    return fail(BSGA_ERR_INVALID_ARG, "%s: softmax_scale must be finite and > 0", fn);
+  const int64_t nb = ceil_div(n_tokens, block);
+  if (kv_idx || kv_cnt) {
+    if (!kv_idx || !kv_cnt) return fail(BSGA_ERR_INVALID_ARG, "%s: kv_idx and kv_cnt must both be given", fn);
+    if (idx_stride < nb)
+      return fail(BSGA_ERR_INVALID_ARG, "%s: idx_stride (%d) must be >= number of key blocks (%lld)", fn, idx_stride,
+                  (long long)nb);
+  }
+  const size_t need = attn_workspace(dtype, heads, n_tokens);
+  if (need > 0) {
+    if (!workspace) return fail(BSGA_ERR_WORKSPACE, "%s: workspace is null, %zu bytes needed", fn, need);
+    if (workspace_bytes < need)
+      return fail(BSGA_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", fn, workspace_bytes, need);
+    if (!aligned16(workspace)) return fail(BSGA_ERR_INVALID_ARG, "%s: workspace must be 16-byte aligned", fn);
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (dtype == BSGA_BF16)
+    return launch_attn_bf16(q, k, v, heads, n_tokens, block, softmax_scale, kv_idx, kv_cnt, idx_stride, out, lse,
+                            workspace, s);
+  return launch_attn_fp32(static_cast<const float*>(q), static_cast<const float*>(k), static_cast<const float*>(v),
+                          heads, n_tokens, block, softmax_scale, kv_idx, kv_cnt, idx_stride,
+                          static_cast<float*>(out), lse, s);
+}
+
+}  // namespace bsga
+
+using namespace bsga;
+
+extern "C" {
+
+int bsga_version(void) { return 1; }
+
+const char* bsga_last_error(void) { return g_err; }
+
+int bsga_pool_qk(const void* q, const void* k, int dtype, int heads, int64_t n_tokens, int head_dim, int block,
+                 double* q_pool, double* k_pool, void* stream) {
+  const char* fn = "bsga_pool_qk";
+  clear_error();
+  if (int rc = check_shape(fn, dtype, heads, n_tokens, head_dim)) return rc;
+  if (int rc = check_block(fn, block)) return rc;
+  if ((q == nullptr) != (q_pool == nullptr) || (k == nullptr) != (k_pool == nullptr))
+    return fail(BSGA_ERR_INVALID_ARG, "%s: each input must come with its output (q with q_pool, k with k_pool)", fn);
+  if (!q && !k) return fail(BSGA_ERR_INVALID_ARG, "%s: nothing to pool (q and k are both null)", fn);
+  if ((q && !aligned16(q)) || (k && !aligned16(k)) || (q_pool && !aligned16(q_pool)) || (k_pool && !aligned16(k_pool)))
+    return fail(BSGA_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", fn);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (q)
+    if (int rc = launch_pool(q, dtype, heads, n_tokens, block, q_pool, s)) return rc;
+  if (k)
+    if (int rc = launch_pool(k, dtype, heads, n_tokens, block, k_pool, s)) return rc;
+  return BSGA_OK;
+}
+
+int bsga_select_blocks(const double* q_pool, const double* k_pool, int heads, int nb_q, int nb_k, int head_dim,
+                       double score_scale, double tau, double rho, const uint8_t* force_q, const uint8_t* force_k,
+                       uint32_t* mask_bits, int32_t* kv_idx, int32_t* kv_cnt, int idx_stride, void* stream) {
+  const char* fn = "bsga_select_blocks";
+  clear_error();
+  if (!q_pool || !k_pool) return fail(BSGA_ERR_INVALID_ARG, "%s: q_pool and k_pool must be non-null", fn);
+  if (!aligned16(q_pool) || !aligned16(k_pool))
+    return fail(BSGA_ERR_INVALID_ARG, "%s: q_pool and k_pool must be 16-byte aligned", fn);
+  if (heads < 1 || heads > 65535) return fail(BSGA_ERR_INVALID_ARG, "%s: heads must be in [1, 65535], got %d", fn, heads);
+  if (head_dim != 64) return fail(BSGA_ERR_UNSUPPORTED, "%s: head_dim must be 64, got %d", fn, head_dim);
+  if (nb_q < 1) return fail(BSGA_ERR_INVALID_ARG, "%s: nb_q must be >= 1, got %d", fn, nb_q);
+  if (nb_k < 1) return fail(BSGA_ERR_INVALID_ARG, "%s: nb_k must be >= 1, got %d", fn, nb_k);
+  if (nb_k > 4096) return fail(BSGA_ERR_UNSUPPORTED, "%s: nb_k above 4096 is not supported, got %d", fn, nb_k);
+  if (!isfinite(score_scale)) return fail(BSGA_ERR_INVALID_ARG, "%s: score_scale must be finite", fn);
+  if (!(tau >= 0.0)) return fail(BSGA_ERR_INVALID_ARG, "%s: tau must be >= 0", fn);
+  if (!(rho >= 0.0 && rho <= 1.0)) return fail(BSGA_ERR_INVALID_ARG, "%s: rho must be in [0, 1]", fn);
+  if (kv_idx && idx_stride < nb_k)
+    return fail(BSGA_ERR_INVALID_ARG, "%s: idx_stride (%d) must be >= nb_k (%d)", fn, idx_stride, nb_k);
+  if (!mask_bits && !kv_idx && !kv_cnt) return fail(BSGA_ERR_INVALID_ARG, "%s: no output requested", fn);
+  // k = floor(B (1 - rho)) in binary64, as the definition is written.
+  const int k_floor = static_cast<int>(floor(static_cast<double>(nb_k) * (1.0 - rho)));
+  return launch_select(q_pool, k_pool, heads, nb_q, nb_k, score_scale, tau, k_floor, force_q, force_k, mask_bits,
+                       kv_idx, kv_cnt, idx_stride, static_cast<hipStream_t>(stream));
+}
+
+size_t bsga_attn_workspace_bytes(int dtype, int heads, int64_t n_tokens, int head_dim) {
+  if ((dtype != BSGA_BF16 && dtype != BSGA_FP32) || heads < 1 || n_tokens < 1 || head_dim != 64) return 0;
+  return attn_workspace(dtype, heads, n_tokens);
+}
+
+int bsga_sparse_attn(const void* q, const void* k, const void* v, int dtype, int heads, int64_t n_tokens,
+                     int head_dim, int block, float softmax_scale, const int32_t* kv_idx, const int32_t* kv_cnt,
+                     int idx_stride, void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!kv_idx || !kv_cnt) {
+    clear_error();
+    return fail(BSGA_ERR_INVALID_ARG, "bsga_sparse_attn: kv_idx and kv_cnt must be non-null");
+  }
+  return attn_common("bsga_sparse_attn", q, k, v, dtype, heads, n_tokens, head_dim, block, softmax_scale, kv_idx,
+                     kv_cnt, idx_stride, out, lse, workspace, workspace_bytes, stream);
+}
+
+int bsga_dense_attn(const void* q, const void* k, const void* v, int dtype, int heads, int64_t n_tokens,
+                    int head_dim, float softmax_scale, void* out, float* lse, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+  const int block = (dtype == BSGA_FP32) ? 64 : 128;
+  return attn_common("bsga_dense_attn", q, k, v, dtype, heads, n_tokens, head_dim, block, softmax_scale, nullptr,
+                     nullptr, 0, out, lse, workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"

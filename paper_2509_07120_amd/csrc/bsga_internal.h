@@ -1,0 +1,38 @@
+// Internal declarations shared by the bsga translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "bsga.h"
+
+namespace bsga {
+
+// Records a message for bsga_last_error() and returns `code`.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
+// Turns a HIP status into a bsga return code (records the HIP error string).
+int check_hip(hipError_t e, const char* what);
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Kernel launchers.  Arguments are already validated.
+int launch_pool(const void* x, int dtype, int heads, int64_t n_tokens, int block, double* pooled,
+                hipStream_t stream);
+
+int launch_select(const double* q_pool, const double* k_pool, int heads, int nb_q, int nb_k,
+                  double score_scale, double tau, int k_floor, const uint8_t* force_q,
+                  const uint8_t* force_k, uint32_t* mask_bits, int32_t* kv_idx, int32_t* kv_cnt,
+                  int idx_stride, hipStream_t stream);
+
+int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int64_t n_tokens,
+                     int block, float softmax_scale, const int32_t* kv_idx, const int32_t* kv_cnt,
+                     int idx_stride, void* out, float* lse, void* workspace, hipStream_t stream);
+
+int launch_attn_fp32(const float* q, const float* k, const float* v, int heads, int64_t n_tokens,
+                     int block, float softmax_scale, const int32_t* kv_idx, const int32_t* kv_cnt,
+                     int idx_stride, float* out, float* lse, hipStream_t stream);
+
+}  // namespace bsga

@@ -1,0 +1,80 @@
+"""Shared helpers for the GPU parity tests: tensor marshalling and the mask comparison rule."""
+import math
+
+import numpy as np
+import torch
+
+from oracle import bsga_oracle as O
+
+
+def to_device(x: np.ndarray, dtype: str) -> torch.Tensor:
+    """float32 numpy values (already rounded to `dtype`) -> device tensor of that dtype."""
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    if dtype == "bf16":
+        t = t.to(torch.bfloat16)  # exact: the values are bf16-representable
+    return t.cuda()
+
+
+def bits_to_mask(bits: torch.Tensor, nbk: int) -> np.ndarray:
+    b = bits.cpu().numpy().view(np.uint32)
+    H, nbq, words = b.shape
+    J = np.arange(nbk)
+    return ((b[:, :, J // 32] >> (J % 32).astype(np.uint32)) & 1).astype(bool)
+
+
+def lists_to_mask(kv_idx: torch.Tensor, kv_cnt: torch.Tensor, nbk: int) -> np.ndarray:
+    idx = kv_idx.cpu().numpy()
+    cnt = kv_cnt.cpu().numpy()
+    H, nbq, _ = idx.shape
+    mask = np.zeros((H, nbq, nbk), dtype=bool)
+    for h in range(H):
+        for I in range(nbq):
+            js = idx[h, I, :cnt[h, I]]
+            assert (np.diff(js) > 0).all(), "index list must be strictly ascending"
+            assert js.size == 0 or (js[0] >= 0 and js[-1] < nbk)
+            mask[h, I, js] = True
+    return mask
+
+
+def unexcused_mask_mismatches(gpu_mask, ora_mask, logits, probs, tau, rho, eps=1e-5):
+    """Counts (unexcused, excused) disagreements.  A disagreement on block J of a row is
+    excused only if J's logit is within eps of the logit of the last kept or first dropped
+    block of the oracle's ranking, or J is one of those two and the cumulative mass at the
+    cut is within eps of tau."""
+    bad = np.argwhere(gpu_mask != ora_mask)
+    unexcused = excused = 0
+    for h, I, J in bad:
+        sel = O.select_row(probs[h, I], tau, rho)
+        lg = logits[h, I]
+        n = sel.n_keep
+        last_kept = sel.order[n - 1]
+        first_drop = sel.order[n] if n < lg.size else None
+        ok = abs(lg[J] - lg[last_kept]) <= eps or (first_drop is not None and abs(lg[J] - lg[first_drop]) <= eps)
+        if not ok and (J == last_kept or J == first_drop):
+            c_n = sel.cum[n - 1]
+            c_nm1 = sel.cum[n - 2] if n >= 2 else 0.0
+            ok = abs(c_n - tau) <= eps or abs(c_nm1 - tau) <= eps
+        if ok:
+            excused += 1
+        else:
+            unexcused += 1
+    return unexcused, excused
+
+
+def oracle_mask_pipeline(q, k, b, tau, rho, score_scale=None):
+    d = q.shape[-1]
+    if score_scale is None:
+        score_scale = 1.0 / math.sqrt(d)
+    qp, kp = O.pool_blocks(q, b), O.pool_blocks(k, b)
+    logits = O.block_logits(qp, kp, score_scale)
+    probs = O.block_softmax(logits)
+    mask = O.select_blocks(probs, tau, rho)
+    return qp, kp, logits, probs, mask
+
+
+def attn_errors(got: torch.Tensor, want: np.ndarray):
+    """max-abs and mean-abs error over the rows the oracle computed (non-NaN rows)."""
+    g = got.float().cpu().numpy().astype(np.float64)
+    sel = ~np.isnan(want[..., 0])
+    diff = np.abs(g[sel] - want[sel])
+    return float(diff.max()), float(diff.mean())

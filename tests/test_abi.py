@@ -1,0 +1,106 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header
+declares, and rejects bad arguments before touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "bsga.h")
+
+
+@pytest.fixture(scope="module")
+def B():
+    import paper_2509_07120_amd as pkg
+    return pkg
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bsga_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(B):
+    names = _declared_functions()
+    assert set(names) == set(B.EXPORTED_SYMBOLS)
+    raw = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(raw, n), n
+    assert B.lib.bsga_version() == 1
+
+
+def test_header_compiles_as_plain_c(tmp_path):
+    src = tmp_path / "t.c"
+    src.write_text('#include "bsga.h"\nint main(void){return BSGA_OK;}\n')
+    import subprocess
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), "-c", str(src),
+                    "-o", str(tmp_path / "t.o")], check=True)
+
+
+def _err(B):
+    return B.lib.bsga_last_error().decode()
+
+
+A = 0x1000  # a fake, 16-byte aligned, non-null pointer; validation must fail before it is used
+
+
+def test_pool_argument_errors(B):
+    L = B.lib
+    assert L.bsga_pool_qk(None, None, 0, 16, 100, 64, 64, None, None, None) == 1 and "nothing to pool" in _err(B)
+    assert L.bsga_pool_qk(A, A, 7, 16, 100, 64, 64, A, A, None) == 1 and "dtype" in _err(B)
+    assert L.bsga_pool_qk(A, A, 0, 0, 100, 64, 64, A, A, None) == 1 and "heads" in _err(B)
+    assert L.bsga_pool_qk(A, A, 0, 16, 0, 64, 64, A, A, None) == 1 and "n_tokens" in _err(B)
+    assert L.bsga_pool_qk(A, A, 0, 16, 100, 128, 64, A, A, None) == 2 and "head_dim" in _err(B)
+    assert L.bsga_pool_qk(A, A, 0, 16, 100, 64, 32, A, A, None) == 2 and "block" in _err(B)
+    assert L.bsga_pool_qk(A, A, 0, 16, 100, 64, 64, None, A, None) == 1 and "output" in _err(B)
+    assert L.bsga_pool_qk(A + 4, A, 0, 16, 100, 64, 64, A, A, None) == 1 and "aligned" in _err(B)
+
+
+def test_select_argument_errors(B):
+    L = B.lib
+    ok = dict(h=16, nbq=10, nbk=10, d=64, s=0.125, tau=0.9, rho=1.0)
+
+    def call(q=A, k=A, h=16, nbq=10, nbk=10, d=64, s=0.125, tau=0.9, rho=1.0, bits=A, idx=A, cnt=A, stride=10):
+        return L.bsga_select_blocks(q, k, h, nbq, nbk, d, s, tau, rho, None, None, bits, idx, cnt, stride, None)
+
+    assert call(q=None) == 1
+    assert call(nbk=0) == 1 and "nb_k" in _err(B)
+    assert call(nbk=4097, stride=4097) == 2 and "4096" in _err(B)
+    assert call(d=32) == 2
+    assert call(tau=-0.1) == 1 and "tau" in _err(B)
+    assert call(tau=float("nan")) == 1
+    assert call(rho=1.5) == 1 and "rho" in _err(B)
+    assert call(s=float("inf")) == 1
+    assert call(stride=9) == 1 and "idx_stride" in _err(B)
+    assert call(bits=None, idx=None, cnt=None) == 1 and "no output" in _err(B)
+
+
+def test_attention_argument_errors(B):
+    L = B.lib
+
+    def sparse(q=A, k=A, v=A, dt=0, h=16, n=1000, d=64, b=128, sc=0.125, idx=A, cnt=A, stride=8, out=A, ws=A,
+               wsb=1 << 30):
+        return L.bsga_sparse_attn(q, k, v, dt, h, n, d, b, sc, idx, cnt, stride, out, None, ws, wsb, None)
+
+    assert sparse(idx=None) == 1 and "kv_idx" in _err(B)
+    assert sparse(v=None) == 1
+    assert sparse(b=32) == 2
+    assert sparse(sc=0.0) == 1 and "softmax_scale" in _err(B)
+    assert sparse(stride=7) == 1 and "idx_stride" in _err(B)
+    assert sparse(ws=None) == 3 and "workspace" in _err(B)
+    assert sparse(wsb=1024) == 3 and "needed" in _err(B)
+    assert sparse(n=(1 << 24) + 1, stride=1 << 20) == 2
+    assert L.bsga_dense_attn(A, A, A, 0, 16, 1000, 64, 0.125, None, None, A, 1 << 30, None) == 1
+    assert L.bsga_dense_attn(A, A, A, 3, 16, 1000, 64, 0.125, A, None, A, 1 << 30, None) == 1
+    assert L.bsga_dense_attn(A, A, A, 0, 16, 1000, 64, 0.125, A, None, A, 16, None) == 3
+
+
+def test_workspace_size(B):
+    import torch
+    assert B.bsga_attn_workspace_bytes(torch.bfloat16, 16, 137400) == 16 * 1074 * 128 * 64 * 2
+    assert B.bsga_attn_workspace_bytes(torch.bfloat16, 1, 1) == 128 * 64 * 2
+    assert B.bsga_attn_workspace_bytes(torch.float32, 16, 2748) == 0
+    assert B.lib.bsga_attn_workspace_bytes(0, 0, 100, 64) == 0
+    assert B.lib.bsga_attn_workspace_bytes(0, 16, 100, 32) == 0

@@ -127,6 +127,14 @@ def generate(cfg: WorkloadConfig, base_seed: int = 0, heads: int | None = None, 
     q = np.empty((H, N, HEAD_DIM), dtype=np.float32)
     k = np.empty_like(q)
     v = np.empty_like(q)
-    for h in range(H):
+    def fill(h):
         q[h], k[h], v[h] = generate_head(cfg, h, base_seed, frames)
+
+    if H > 1 and N >= 20000:  # numpy's generators release the GIL on large fills
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(8, H)) as pool:
+            list(pool.map(fill, range(H)))
+    else:
+        for h in range(H):
+            fill(h)
     return q, k, v
