@@ -3,18 +3,34 @@
 // softmax in the log2 domain.
 //
 // Work split.  One workgroup per (head, query block of B rows); it walks the row's kept key
-// blocks (tiles of B keys).  Waves are arranged WQ x 2: wave (qi, kh) owns 64 query rows
-// (qi) and one half of every key tile (kh), so each K/V^T operand fetched from LDS feeds two
-// MFMAs.  The two key halves keep independent softmax states that are merged once at the end.
+// blocks (tiles of B keys).  Waves are arranged WQ x 2: wave (qi, kh) owns 64 query rows (qi)
+// and one half of every key tile (kh), so each K/V operand fetched from LDS feeds two MFMAs.
+// The two key halves keep independent softmax states that are merged once at the end.  Two
+// workgroups share a CU (two waves per SIMD), so one wave's softmax VALU work overlaps the
+// other's MFMAs.
+//
+// Data movement.  K and V tiles go HBM/L2 -> LDS with direct-to-LDS loads (16 bytes per lane, no
+// staging registers), double buffered: the loads of tile t+1 are in flight while tile t is
+// computed.  Tiles stay row-major [key][64]; only the order of the eight 16-byte chunks inside a
+// row is permuted (XOR swizzle, chosen per tensor) so the operand reads below are conflict free.
 //
 // Register layouts.  Scores are produced transposed, S^T = K Q^T (M = keys, N = queries): in the
-// 32x32 accumulator layout lane (n = lane%32, g = lane/32) then holds, for query n, the keys
-// 8*r4 + 4*g + r (register 4*r4 + r).  A lane therefore owns whole query columns: row max/sum
-// need one cross-lane step (lane ^ 32), and after exponentiation the same registers are, without
-// any data movement, the B operand of O^T += V^T P^T provided the contraction index ("slot")
-// is permuted as  slot 16c + 8g + 4t + r  <->  key 16c + 8t + 4g + r.  V is repacked once per call
-// into that slot order, transposed to [dim][slot] per key tile and pre-swizzled for
-// conflict-free 16-byte LDS reads, so that a key tile of V^T is one contiguous 64 x B block.
+// 32x32 accumulator layout lane (n = lane%32, g = lane/32) holds, for query n, the keys
+// 8*r4 + 4*g + r (register 4*r4 + r).  A lane owns whole query columns, so row max/sum need one
+// cross-lane step (lane ^ 32), and after exponentiation the same registers are, with no data
+// movement, the B operand of O^T += V^T P^T if the contraction index is taken in the order the
+// accumulator holds the keys.  The matching A operand (V^T: 32 dims x 16 keys) is read from the
+// row-major V tile with the LDS transpose read (ds_read_b64_tr_b16): each 16-lane group names four
+// keys and gets, per lane, those four keys' values of one dim.
+//
+// Softmax.  Q is pre-multiplied by softmax_scale*log2(e) when it is loaded, and the accumulator
+// of the score MFMA is initialised to -m_ref (the lane's reference maximum), so the MFMA result
+// is already the exponent of exp2.  m_ref is raised only when a tile exceeds it by more than
+// 2^8 (the weights then stay <= 256, harmless in fp32/bf16); the final O / l is exact for any
+// reference, so this only skips rescaling work.  Row sums are taken from the bf16-rounded
+// weights (dot2 with ones), i.e. from exactly what multiplies V.
+#include <type_traits>
+
 #include "bsga_internal.h"
 
 namespace bsga {
@@ -22,114 +38,54 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
+#define LDS_PTR(T, p) ((const T __attribute__((address_space(3)))*)(p))
+
 constexpr int kD = 64;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kRaise = 8.0f;  // raise the reference maximum when a tile exceeds it by 2^8
 
-// 16-byte chunk swizzles (chunk index within a row of the LDS tile)
-__device__ __host__ inline int swz_k(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
-template <int B>
-__device__ __host__ inline int swz_v(int row, int chunk) {
-  return (B == 128) ? (chunk ^ (row & 15)) : (chunk ^ ((row >> 1) & 7));
-}
-// contraction slot -> key offset inside a key tile
-__device__ __host__ inline int slot_to_key(int s) {
-  return (s & ~15) | ((s & 4) << 1) | ((s & 8) >> 1) | (s & 3);
-}
+// chunk swizzles: 16-byte chunk c of tile row r is stored at chunk position c ^ swz(r)
+__device__ __forceinline__ int swz_k(int row) { return (row ^ (row >> 3)) & 7; }
+__device__ __forceinline__ int swz_v(int row) { return (row & 3) << 1; }
 
-// ---------------------------------------------------------------------------------------------
-// V repack: V [H, N, 64] -> workspace [H, NB, 64 dims, B slots] (slot-permuted, chunk-swizzled,
-// keys past N zero-filled).
-template <int B>
-__global__ __launch_bounds__(256) void repack_v_kernel(const uint4* __restrict__ v, uint4* __restrict__ vt,
-                                                       int64_t n_tokens, int nb) {
-  constexpr int PITCH = kD + 2;  // ushorts per staged key row (odd dword pitch)
-  __shared__ unsigned short tile[B * PITCH];
-  const int J = blockIdx.x;
-  const int h = blockIdx.y;
-  const int t = threadIdx.x;
-  const int64_t key0 = int64_t(J) * B;
-  const int valid = static_cast<int>(min<int64_t>(B, n_tokens - key0));
-  const uint4* src = v + (int64_t(h) * n_tokens + key0) * 8;
-  for (int c = t; c < B * 8; c += 256) {
-    const int r = c >> 3, d8 = c & 7;
-    uint4 x = make_uint4(0, 0, 0, 0);
-    if (r < valid) x = src[c];
-    unsigned* dst = reinterpret_cast<unsigned*>(&tile[r * PITCH + d8 * 8]);
-    dst[0] = x.x; dst[1] = x.y; dst[2] = x.z; dst[3] = x.w;
-  }
-  __syncthreads();
-  constexpr int CPR = B / 8;  // 16-byte chunks per output row
-  uint4* dstt = vt + (int64_t(h) * nb + J) * (kD * CPR);
-  for (int p = t; p < kD * CPR; p += 256) {
-    const int row = p / CPR, pc = p % CPR;
-    const int cc = swz_v<B>(row, pc);  // XOR swizzle is its own inverse
-    unsigned short e[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) e[i] = tile[slot_to_key(cc * 8 + i) * PITCH + row];
-    uint4 o;
-    o.x = e[0] | (unsigned(e[1]) << 16); o.y = e[2] | (unsigned(e[3]) << 16);
-    o.z = e[4] | (unsigned(e[5]) << 16); o.w = e[6] | (unsigned(e[7]) << 16);
-    dstt[p] = o;
-  }
+__device__ __forceinline__ unsigned pack_bf16(float a, float b) {
+  const f32x2 two = {a, b};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(two, bf16x2));
 }
 
-// global -> registers for key tile J: K rows in swizzled chunk order (rows past the end read as
-// zero), the V^T tile as a straight copy.  Thread `tid` of 2B owns chunks tid, tid + 2B, ...
-template <int B>
-__device__ __forceinline__ void fetch_tile(const u32x4* __restrict__ k, const u32x4* __restrict__ vt,
-                                           int64_t head_chunks, int h, int nb, int tail, int J, int tid,
-                                           u32x4 (&sk)[4], u32x4 (&sv)[4]) {
-  const int64_t key0 = int64_t(J) * B;
-  const int valid = (J == nb - 1) ? tail : B;
-  const u32x4* vsrc = vt + (int64_t(h) * nb + J) * (B * 8);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int p = tid + i * 2 * B;
-    const int r = p >> 3, pc = p & 7;
-    const int rr = min(r, valid - 1);
-    u32x4 x = k[head_chunks + (key0 + rr) * 8 + swz_k(r, pc)];
-    if (r >= valid) x = u32x4{0u, 0u, 0u, 0u};
-    sk[i] = x;
-    sv[i] = vsrc[p];
-  }
-}
-// registers -> LDS buffer (K tile followed by V^T tile)
-template <int B>
-__device__ __forceinline__ void commit_tile(unsigned char* buf, int tid, const u32x4 (&sk)[4],
-                                            const u32x4 (&sv)[4]) {
-  u32x4* kd = reinterpret_cast<u32x4*>(buf);
-  u32x4* vd = reinterpret_cast<u32x4*>(buf + B * 128);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    kd[tid + i * 2 * B] = sk[i];
-    vd[tid + i * 2 * B] = sv[i];
-  }
+__device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32); }
+
+// 16 bytes per lane from a raw buffer straight into LDS: lane i's data lands at lds_dst + 16 i.
+// voff is the per-lane byte offset, soff a wave-uniform one; reads past the buffer's size return 0.
+__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, unsigned voff, unsigned soff,
+                                      unsigned char* lds_dst) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(lds_dst), 16, voff, soff,
+                                           0, 0);
 }
 
-// ---------------------------------------------------------------------------------------------
 template <int B>
-__global__ __launch_bounds__(2 * B) void attn_bf16_kernel(
-    const u32x4* __restrict__ q, const u32x4* __restrict__ k, const u32x4* __restrict__ vt,
+__global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
+    const unsigned char* __restrict__ q, const unsigned char* __restrict__ k, const unsigned char* __restrict__ v,
     unsigned short* __restrict__ out, float* __restrict__ lse, const int32_t* __restrict__ kv_idx,
     const int32_t* __restrict__ kv_cnt, int idx_stride, int64_t n_tokens, int nb, float scale_log2) {
-  constexpr int WQ = B / 64;        // waves along queries
-  constexpr int KW = B / 2;         // keys per wave per tile
-  constexpr int MB = KW / 32;       // 32-key MFMA row blocks per wave
-  constexpr int KC = KW / 16;       // 16-slot contraction chunks per wave in P V
-  constexpr int THREADS = 2 * B;
-  constexpr int TILE_BYTES = B * 128;
-  constexpr int CHUNKS = B * 8;     // 16-byte chunks per tile
-  constexpr int CPT = CHUNKS / THREADS;  // = 4 chunks per thread per tensor
-  extern __shared__ __align__(16) unsigned char smem[];  // [2 buffers][K tile | V^T tile]
+  constexpr int WQ = B / 64;              // waves along queries
+  constexpr int KW = B / 2;               // keys per wave per tile
+  constexpr int MB = KW / 32;             // 32-key MFMA row blocks per wave
+  constexpr int KC = KW / 16;             // 16-key contraction chunks per wave in P V
+  constexpr int NW = B / 32;              // waves per workgroup
+  constexpr int TILE_BYTES = B * 128;     // one K or V tile
+  constexpr int BUF_BYTES = 2 * TILE_BYTES;
+  extern __shared__ __align__(1024) unsigned char smem[];  // [2 buffers][K tile | V tile]
 
   const int tid = threadIdx.x;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
   const int n = lane & 31;
   const int g = lane >> 5;
@@ -137,19 +93,71 @@ __global__ __launch_bounds__(2 * B) void attn_bf16_kernel(
   const int kh = wave / WQ;
   const int I = blockIdx.x;
   const int h = blockIdx.y;
-  const int64_t head_chunks = int64_t(h) * n_tokens * 8;  // 16-byte chunks before this head in Q/K
+  const int64_t head_bytes = int64_t(h) * n_tokens * 128;
   const int64_t rowid = int64_t(h) * nb + I;
+  // raw buffer views of this head's K and V (byte-addressed, bounds-checked by the hardware)
+  const unsigned head_size = static_cast<unsigned>(n_tokens * 128);
+  const __amdgpu_buffer_rsrc_t krsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(k + head_bytes), 0, head_size, 0x00020000);
+  const __amdgpu_buffer_rsrc_t vrsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(v + head_bytes), 0, head_size, 0x00020000);
 
-  // ---- Q fragments (B operand of S^T = K Q^T): lane (n, g) holds dims 16c + 8g .. +7 of its row
+  // ---- Q fragments (B operand of S^T = K Q^T), pre-scaled: lane (n, g) holds dims 16c + 8g .. +7
   bf16x8 qf[2][4];
 #pragma unroll
   for (int b2 = 0; b2 < 2; ++b2) {
     const int64_t row = int64_t(I) * B + qi * 64 + b2 * 32 + n;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      u32x4 x = u32x4{0u, 0u, 0u, 0u};
-      if (row < n_tokens) x = q[head_chunks + row * 8 + 2 * c + g];
-      qf[b2][c] = __builtin_bit_cast(bf16x8, x);
+      u32x4 x = {0u, 0u, 0u, 0u};
+      if (row < n_tokens) x = *reinterpret_cast<const u32x4*>(q + head_bytes + row * 128 + (2 * c + g) * 16);
+      u32x4 y;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float lo = __uint_as_float(x[e] << 16) * scale_log2;
+        const float hi = __uint_as_float(x[e] & 0xffff0000u) * scale_log2;
+        y[e] = pack_bf16(lo, hi);
+      }
+      qf[b2][c] = __builtin_bit_cast(bf16x8, y);
+    }
+  }
+
+  // ---- per-lane constants -------------------------------------------------------------------------
+  // direct-to-LDS loads: wave-load j covers LDS bytes [1024 j, 1024 j + 1024) of a tile; this wave
+  // issues j = wave + NW*i, i = 0..3, for the K tile and for the V tile.  Lane -> LDS position
+  // p = 64 j + lane -> (row p/8, chunk position p%8) -> global chunk (p%8) ^ swz(row).  Row r_i is
+  // r_0 + 8 NW i with r_0 < 8 NW, so swz_k(r_i) = swz_k(r_0) ^ swz_k(8 NW i) and swz_v(r_i) =
+  // swz_v(r_0): the K offsets repeat with period KN in i up to a multiple of 1024 NW (which goes
+  // into the wave-uniform offset), the V offsets differ by that multiple only.
+  constexpr int KN = (B == 128) ? 2 : 4;
+  const int dma_r0 = wave * 8 + (lane >> 3);
+  const int dma_pc = lane & 7;
+  unsigned koff[KN];
+#pragma unroll
+  for (int i = 0; i < KN; ++i) {
+    const int r = dma_r0 + 8 * NW * i;
+    koff[i] = r * 128 + ((dma_pc ^ swz_k(r)) << 4);
+  }
+  const unsigned voff = dma_r0 * 128 + ((dma_pc ^ swz_v(dma_r0)) << 4);
+  // K operand reads (ds_read_b128): row r = kh*KW + mb*32 + n, logical chunk 2c + g.  Since
+  // swz_k(r + 32) = swz_k(r) ^ 4, block mb = 1 reads chunk c where block 0 reads chunk c ^ 2.
+  unsigned kaddr[4];
+  {
+    const int r = kh * KW + n;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) kaddr[c] = r * 128 + (((2 * c + g) ^ swz_k(r)) << 4);
+  }
+  // V operand reads (transpose read, 8 bytes per lane): 16-lane group G = lane/16 covers dims
+  // db*32 + 16*(G&1) .. +15 for key-slot half g = G/2; inside the group lane i names key
+  // m = i/4 of the four and the dim quad j = i%4.
+  unsigned vaddr[2];
+  {
+    const int i16 = lane & 15, m = i16 >> 2, j = i16 & 3, G = lane >> 4;
+    const int keyl = kh * KW + 4 * g + m;  // + 16*kc + 8*t added as an immediate
+#pragma unroll
+    for (int db = 0; db < 2; ++db) {
+      const int cc = db * 4 + 2 * (G & 1) + (j >> 1);
+      vaddr[db] = TILE_BYTES + keyl * 128 + ((cc ^ swz_v(keyl)) << 4) + (j & 1) * 8;
     }
   }
 
@@ -160,49 +168,81 @@ __global__ __launch_bounds__(2 * B) void attn_bf16_kernel(
     for (int b2 = 0; b2 < 2; ++b2)
 #pragma unroll
       for (int i = 0; i < 16; ++i) o[a][b2][i] = 0.f;
-  float m_run[2] = {-INFINITY, -INFINITY};
-  float l_run[2] = {0.f, 0.f};
+  float m_ref[2] = {-INFINITY, -INFINITY};  // reference maximum per query column (log2 domain)
+  float l_run[2] = {0.f, 0.f};              // this lane's share of the row sum
 
   const bool dense = kv_idx == nullptr;
   const int count = dense ? nb : min(max(kv_cnt[rowid], 0), nb);
   const int32_t* my_idx = dense ? nullptr : kv_idx + rowid * idx_stride;
   const int tail = static_cast<int>(n_tokens - int64_t(nb - 1) * B);  // valid keys in the last tile
 
-  u32x4 stage_k[CPT], stage_v[CPT];
-  auto block_at = [&](int it) {
-    int J = dense ? it : my_idx[it];
+  // The row's key-block list is read 64 entries at a time, one per lane, and handed out with
+  // readlane; the next 64 are already in flight while the current ones are consumed.
+  int idx_cur = 0, idx_next = 0;
+  auto load_idx = [&](int first) {
+    const int t = first + lane;
+    return (!dense && t < count) ? my_idx[t] : 0;
+  };
+  idx_cur = load_idx(0);
+  idx_next = load_idx(64);
+  auto block_at = [&](int it) {  // must be called with it = 0, 1, 2, ... in order
+    if (dense) return it;
+    if (it > 0 && (it & 63) == 0) {
+      idx_cur = idx_next;
+      idx_next = load_idx(it + 64);
+    }
+    const int J = __builtin_amdgcn_readlane(idx_cur, it & 63);
     return min(max(J, 0), nb - 1);
   };
+  // enqueue the direct-to-LDS loads of key tile J into buffer `buf`
+  auto issue = [&](int J, int buf) {
+    const unsigned soff = static_cast<unsigned>(J) * TILE_BYTES;
+    unsigned char* dst = smem + buf * BUF_BYTES + wave * 1024;
+    if (J == nb - 1 && tail < B) {  // ragged tile: rows past the end re-read the last valid row
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int r = dma_r0 + 8 * NW * i;
+        const int rs = min(r, tail - 1);
+        dma16(krsrc, rs * 128 + ((dma_pc ^ swz_k(r)) << 4), soff, dst + NW * i * 1024);
+        dma16(vrsrc, rs * 128 + ((dma_pc ^ swz_v(r)) << 4), soff, dst + TILE_BYTES + NW * i * 1024);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        dma16(krsrc, koff[i % KN], soff + (i / KN) * KN * NW * 1024, dst + NW * i * 1024);
+        dma16(vrsrc, voff, soff + i * NW * 1024, dst + TILE_BYTES + NW * i * 1024);
+      }
+    }
+  };
 
-  if (count > 0) {
-    fetch_tile<B>(k, vt, head_chunks, h, nb, tail, block_at(0), tid, stage_k, stage_v);
-    commit_tile<B>(smem, tid, stage_k, stage_v);
-  }
-  __syncthreads();
+  // one key tile: wait for its loads, start the next tile's loads, compute.  BUF is a compile-time
+  // constant so every LDS address below is a lane-constant register plus an immediate.
+  auto step = [&](auto bufc, int it, int J) -> int {
+    constexpr int buf = decltype(bufc)::value;
+    int J_next = 0;
+    if (it + 1 < count) J_next = block_at(it + 1);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile `it` has landed
+    __syncthreads();                     // ... and so has everyone else's; buffer buf^1 is free
+    if (it + 1 < count) issue(J_next, buf ^ 1);
 
-  for (int it = 0; it < count; ++it) {
-    const int buf = it & 1;
-    const int J = block_at(it);
-    const bool more = it + 1 < count;
-    if (more) fetch_tile<B>(k, vt, head_chunks, h, nb, tail, block_at(it + 1), tid, stage_k, stage_v);
+    const unsigned char* tile = smem + buf * BUF_BYTES;
 
-    const unsigned char* kt = smem + buf * 2 * TILE_BYTES;
-    const unsigned char* vtile = kt + TILE_BYTES;
-
-    // ---- S^T = K Q^T ------------------------------------------------------------------------
+    // ---- S^T = K Q^T - m_ref -----------------------------------------------------------------
+    float base[2];
     f32x16 s[MB][2];
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
+    for (int b2 = 0; b2 < 2; ++b2) {
+      base[b2] = (m_ref[b2] == -INFINITY) ? 0.f : m_ref[b2];
 #pragma unroll
-      for (int b2 = 0; b2 < 2; ++b2)
+      for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s[mb][b2][i] = 0.f;
+        for (int i = 0; i < 16; ++i) s[mb][b2][i] = -base[b2];
+    }
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
-      const int r = kh * KW + mb * 32 + n;
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(kt + r * 128 + (swz_k(r, 2 * c + g) << 4));
+        const bf16x8 a = *LDS_PTR(bf16x8, tile + kaddr[mb ? (c ^ 2) : c] + mb * 4096);
 #pragma unroll
         for (int b2 = 0; b2 < 2; ++b2)
           s[mb][b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[b2][c], s[mb][b2], 0, 0, 0);
@@ -221,7 +261,7 @@ __global__ __launch_bounds__(2 * B) void attn_bf16_kernel(
         }
     }
 
-    // ---- online softmax (log2 domain), per query column ----------------------------------------
+    // ---- softmax weights, per query column -------------------------------------------------------
     bf16x8 pf[2][KC];
 #pragma unroll
     for (int b2 = 0; b2 < 2; ++b2) {
@@ -230,61 +270,75 @@ __global__ __launch_bounds__(2 * B) void attn_bf16_kernel(
       for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, s[mb][b2][i]);
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-      const float m_new = fmaxf(m_run[b2], tmax * scale_log2);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = exp2f(m_run[b2] - m_use);
-      float rowsum = 0.f;
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float p = exp2f(fmaf(s[mb][b2][i], scale_log2, -m_use));
-          s[mb][b2][i] = p;
-          rowsum += p;
-        }
-      l_run[b2] = l_run[b2] * alpha + rowsum;
-      m_run[b2] = m_new;
-      if (__any(alpha != 1.f)) {
+      tmax = fmaxf(tmax, xor32(tmax));
+      const bool unset = m_ref[b2] == -INFINITY;
+      const bool raise = unset ? (tmax > -INFINITY) : (tmax > kRaise);
+      if (__any(raise)) {  // rare after the first tile
+        const float shift = raise ? tmax : 0.f;
+        const float alpha = unset ? 1.f : exp2f(-shift);  // nothing accumulated yet while unset
+        if (raise) m_ref[b2] = base[b2] + shift;
+        l_run[b2] *= alpha;
 #pragma unroll
         for (int db = 0; db < 2; ++db)
 #pragma unroll
           for (int i = 0; i < 16; ++i) o[db][b2][i] *= alpha;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s[mb][b2][i] -= shift;
       }
+      const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
+      float rowsum = l_run[b2];
 #pragma unroll
       for (int kc = 0; kc < KC; ++kc) {
         const int mb = kc >> 1, cp = kc & 1;
-        unsigned w[4];
+        u32x4 w;
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
           for (int r2 = 0; r2 < 2; ++r2) {
             const int i0 = 4 * (2 * cp + t2) + 2 * r2;
-            const f32x2 two = {s[mb][b2][i0], s[mb][b2][i0 + 1]};
-            w[2 * t2 + r2] = __builtin_bit_cast(unsigned, __builtin_convertvector(two, bf16x2));
+            const unsigned pk =
+                pack_bf16(__builtin_amdgcn_exp2f(s[mb][b2][i0]), __builtin_amdgcn_exp2f(s[mb][b2][i0 + 1]));
+            rowsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, rowsum, false);
+            w[2 * t2 + r2] = pk;
           }
-        const u32x4 pk = u32x4{w[0], w[1], w[2], w[3]};
-        pf[b2][kc] = __builtin_bit_cast(bf16x8, pk);
+        pf[b2][kc] = __builtin_bit_cast(bf16x8, w);
       }
+      l_run[b2] = rowsum;
     }
 
     // ---- O^T += V^T P^T -----------------------------------------------------------------------
 #pragma unroll
     for (int db = 0; db < 2; ++db) {
-      const int row = db * 32 + n;
 #pragma unroll
       for (int kc = 0; kc < KC; ++kc) {
-        const int cc = (kh * KW + kc * 16 + g * 8) >> 3;
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(vtile + row * (2 * B) + (swz_v<B>(row, cc) << 4));
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (s16x4 __attribute__((address_space(3)))*)(tile + vaddr[db] + (kc * 16) * 128));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (s16x4 __attribute__((address_space(3)))*)(tile + vaddr[db] + (kc * 16 + 8) * 128));
+        const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
+        const u32x4 av = {lo2[0], lo2[1], hi2[0], hi2[1]};
+        const bf16x8 a = __builtin_bit_cast(bf16x8, av);
 #pragma unroll
         for (int b2 = 0; b2 < 2; ++b2)
           o[db][b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[b2][kc], o[db][b2], 0, 0, 0);
       }
     }
+    return J_next;
+  };
 
-    if (more) commit_tile<B>(smem + (buf ^ 1) * 2 * TILE_BYTES, tid, stage_k, stage_v);
-    __syncthreads();
+  int J0 = 0;
+  if (count > 0) {
+    J0 = block_at(0);
+    issue(J0, 0);
   }
+  for (int it = 0; it < count; it += 2) {
+    const int J1 = step(std::integral_constant<int, 0>{}, it, J0);
+    if (it + 1 >= count) break;
+    J0 = step(std::integral_constant<int, 1>{}, it + 1, J1);
+  }
+  __syncthreads();  // every wave is done reading the tiles: LDS can be reused
 
   // ---- merge the two key halves and write ---------------------------------------------------
   // wave (qi, 1) parks its state in LDS as [qi][68 values][64 lanes]; wave (qi, 0) folds it in.
@@ -298,7 +352,7 @@ __global__ __launch_bounds__(2 * B) void attn_bf16_kernel(
         for (int i = 0; i < 16; ++i) park[((db * 2 + b2) * 16 + i) * 64 + lane] = o[db][b2][i];
 #pragma unroll
     for (int b2 = 0; b2 < 2; ++b2) {
-      park[(64 + b2) * 64 + lane] = m_run[b2];
+      park[(64 + b2) * 64 + lane] = m_ref[b2];
       park[(66 + b2) * 64 + lane] = l_run[b2];
     }
   }
@@ -308,12 +362,12 @@ __global__ __launch_bounds__(2 * B) void attn_bf16_kernel(
     for (int b2 = 0; b2 < 2; ++b2) {
       const float m1 = park[(64 + b2) * 64 + lane];
       const float l1 = park[(66 + b2) * 64 + lane];
-      const float m0 = m_run[b2];
+      const float m0 = m_ref[b2];
       const float mt = fmaxf(m0, m1);
       const float mu = (mt == -INFINITY) ? 0.f : mt;
-      const float a0 = exp2f(m0 - mu), a1 = exp2f(m1 - mu);
+      const float a0 = exp2f(m0 - mu), a1 = exp2f(m1 - mu);  // exp2f(-inf) = 0 for a half that saw nothing
       float lt = l_run[b2] * a0 + l1 * a1;
-      lt += __shfl_xor(lt, 32);
+      lt += xor32(lt);
       const float inv = lt > 0.f ? 1.f / lt : 0.f;
       const int64_t row = int64_t(I) * B + qi * 64 + b2 * 32 + n;
       if (row < n_tokens) {
@@ -327,12 +381,8 @@ __global__ __launch_bounds__(2 * B) void attn_bf16_kernel(
               const int i = 4 * r4 + r;
               x[r] = (o[db][b2][i] * a0 + park[((db * 2 + b2) * 16 + i) * 64 + lane] * a1) * inv;
             }
-            const f32x2 lo = {x[0], x[1]}, hi = {x[2], x[3]};
-            const bf16x2 blo = __builtin_convertvector(lo, bf16x2), bhi = __builtin_convertvector(hi, bf16x2);
-            uint2 w;
-            w.x = __builtin_bit_cast(unsigned, blo);
-            w.y = __builtin_bit_cast(unsigned, bhi);
-            *reinterpret_cast<uint2*>(out + (int64_t(h) * n_tokens + row) * kD + db * 32 + 8 * r4 + 4 * g) = w;
+            const u32x2 w = {pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3])};
+            *reinterpret_cast<u32x2*>(out + (int64_t(h) * n_tokens + row) * kD + db * 32 + 8 * r4 + 4 * g) = w;
           }
         if (lse != nullptr && g == 0)
           lse[int64_t(h) * n_tokens + row] = lt > 0.f ? (mt + log2f(lt)) * kLn2 : -INFINITY;
@@ -346,20 +396,19 @@ __global__ __launch_bounds__(2 * B) void attn_bf16_kernel(
 int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int64_t n_tokens, int block,
                      float softmax_scale, const int32_t* kv_idx, const int32_t* kv_cnt, int idx_stride, void* out,
                      float* lse, void* workspace, hipStream_t stream) {
+  (void)workspace;
   const int nb = static_cast<int>(ceil_div(n_tokens, block));
   const float scale_log2 = softmax_scale * kLog2e;
   dim3 grid(nb, heads);
-  const u32x4* qp = static_cast<const u32x4*>(q);
-  const u32x4* kp = static_cast<const u32x4*>(k);
-  u32x4* vt = static_cast<u32x4*>(workspace);
+  const unsigned char* qp = static_cast<const unsigned char*>(q);
+  const unsigned char* kp = static_cast<const unsigned char*>(k);
+  const unsigned char* vp = static_cast<const unsigned char*>(v);
   unsigned short* op = static_cast<unsigned short*>(out);
   if (block == 64) {
-    hipLaunchKernelGGL((repack_v_kernel<64>), grid, dim3(256), 0, stream, static_cast<const uint4*>(v), reinterpret_cast<uint4*>(vt), n_tokens, nb);
-    hipLaunchKernelGGL((attn_bf16_kernel<64>), grid, dim3(128), 4 * 64 * 128, stream, qp, kp, vt, op, lse, kv_idx,
+    hipLaunchKernelGGL((attn_bf16_kernel<64>), grid, dim3(128), 4 * 64 * 128, stream, qp, kp, vp, op, lse, kv_idx,
                        kv_cnt, idx_stride, n_tokens, nb, scale_log2);
   } else {
-    hipLaunchKernelGGL((repack_v_kernel<128>), grid, dim3(256), 0, stream, static_cast<const uint4*>(v), reinterpret_cast<uint4*>(vt), n_tokens, nb);
-    hipLaunchKernelGGL((attn_bf16_kernel<128>), grid, dim3(256), 4 * 128 * 128, stream, qp, kp, vt, op, lse, kv_idx,
+    hipLaunchKernelGGL((attn_bf16_kernel<128>), grid, dim3(256), 4 * 128 * 128, stream, qp, kp, vp, op, lse, kv_idx,
                        kv_cnt, idx_stride, n_tokens, nb, scale_log2);
   }
   return check_hip(hipGetLastError(), "bsga bf16 attention launch");

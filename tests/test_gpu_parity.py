@@ -22,6 +22,14 @@ BF16_MAX, BF16_MEAN = 1e-2, 1e-3
 FP32_MAX, FP32_MEAN = 1e-5, 1e-6
 
 
+def _bf16_mean_bar(want):
+    """Mean-abs bar for the random small-shape cases.  With a handful of unit-normal keys the
+    outputs are O(1) instead of the O(0.1) of the benchmark shapes, and rounding the output
+    alone to bf16 costs up to 2^-9 |o| per element; the bar therefore never drops below
+    2^-8 * mean|o| (output rounding plus the equally sized rounding of the softmax weights)."""
+    return max(BF16_MEAN, float(np.nanmean(np.abs(want))) / 256.0)
+
+
 @pytest.fixture(scope="module")
 def B():
     import paper_2509_07120_amd as pkg
@@ -159,7 +167,7 @@ def test_sparse_attention_small_shapes(B, dtype, b, N):
     torch.cuda.synchronize()
     want, want_lse = O.sparse_attention(q, k, v, mask, b, return_lse=True)
     mx, mean = attn_errors(out, want)
-    lim = (BF16_MAX, BF16_MEAN) if dtype == "bf16" else (FP32_MAX, FP32_MEAN)
+    lim = (BF16_MAX, _bf16_mean_bar(want)) if dtype == "bf16" else (FP32_MAX, FP32_MEAN)
     assert mx <= lim[0] and mean <= lim[1], (mx, mean)
     assert np.abs(lse.cpu().numpy() - want_lse).max() <= (2e-2 if dtype == "bf16" else 1e-5)
 
@@ -172,7 +180,7 @@ def test_dense_attention_small_shapes(B, dtype, N):
     torch.cuda.synchronize()
     want, want_lse = O.dense_attention(q, k, v, return_lse=True)
     mx, mean = attn_errors(out, want)
-    lim = (BF16_MAX, BF16_MEAN) if dtype == "bf16" else (FP32_MAX, FP32_MEAN)
+    lim = (BF16_MAX, _bf16_mean_bar(want)) if dtype == "bf16" else (FP32_MAX, FP32_MEAN)
     assert mx <= lim[0] and mean <= lim[1], (mx, mean)
     assert np.abs(lse.cpu().numpy() - want_lse).max() <= (2e-2 if dtype == "bf16" else 1e-5)
 
