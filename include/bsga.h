@@ -86,8 +86,9 @@ int bsga_select_blocks(const double* q_pool, const double* k_pool, int heads, in
                        int32_t* kv_idx, int32_t* kv_cnt, int idx_stride, void* stream);
 
 /*
- * Bytes of device workspace bsga_sparse_attn / bsga_dense_attn need for this shape
- * (a repacked copy of V for the bf16 path; 0 for fp32).  Returns 0 on invalid arguments.
+ * Bytes of device workspace bsga_sparse_attn / bsga_dense_attn need for this shape.  The current
+ * kernels read Q, K and V in place and keep all intermediates on chip, so this is 0 for every
+ * shape (and for invalid arguments); callers should still query it and pass what it asks for.
  */
 size_t bsga_attn_workspace_bytes(int dtype, int heads, int64_t n_tokens, int head_dim);
 
@@ -100,8 +101,9 @@ size_t bsga_attn_workspace_bytes(int dtype, int heads, int64_t n_tokens, int hea
  *   kv_idx   [heads, nb, idx_stride] int32, each row's kept key blocks: distinct, in [0, nb);
  *   kv_cnt   [heads, nb] int32, 1 <= count <= nb (a row with count 0 yields zeros, lse = -inf)
  *   lse      nullable [heads, n_tokens] float32: natural-log sum-exp of each row's kept logits
- *   workspace, workspace_bytes: device scratch of at least bsga_attn_workspace_bytes(...);
- *            contents are overwritten; calls sharing one workspace must be stream-ordered.
+ *   workspace, workspace_bytes: device scratch of at least bsga_attn_workspace_bytes(...) bytes
+ *            (may be NULL / 0 when that is 0); contents are overwritten; calls sharing one
+ *            workspace must be stream-ordered.
  * bf16: products on bf16 MFMA with fp32 accumulation, fp32 online softmax.  softmax_scale > 0.
  * The index lists are trusted to be in range (they come from bsga_select_blocks); block
  * indices are clamped to [0, nb) before use so a corrupt list cannot read out of bounds.

@@ -162,14 +162,8 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   }
 
   f32x16 o[2][2];
-#pragma unroll
-  for (int a = 0; a < 2; ++a)
-#pragma unroll
-    for (int b2 = 0; b2 < 2; ++b2)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o[a][b2][i] = 0.f;
-  float m_ref[2] = {-INFINITY, -INFINITY};  // reference maximum per query column (log2 domain)
-  float l_run[2] = {0.f, 0.f};              // this lane's share of the row sum
+  float m_ref[2];  // reference maximum per query column (log2 domain); unused by the fast pass
+  float l_run[2];  // this lane's share of the row sum
 
   const bool dense = kv_idx == nullptr;
   const int count = dense ? nb : min(max(kv_cnt[rowid], 0), nb);
@@ -183,8 +177,6 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     const int t = first + lane;
     return (!dense && t < count) ? my_idx[t] : 0;
   };
-  idx_cur = load_idx(0);
-  idx_next = load_idx(64);
   auto block_at = [&](int it) {  // must be called with it = 0, 1, 2, ... in order
     if (dense) return it;
     if (it > 0 && (it & 63) == 0) {
@@ -215,10 +207,18 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     }
   };
 
-  // one key tile: wait for its loads, start the next tile's loads, compute.  BUF is a compile-time
+  // One key tile: wait for its loads, start the next tile's loads, compute.  BUF is a compile-time
   // constant so every LDS address below is a lane-constant register plus an immediate.
-  auto step = [&](auto bufc, int it, int J) -> int {
+  //
+  // SAFE = false (fast pass): weights are exp2 of the raw scaled logits, i.e. the softmax reference
+  // is 0 for every row.  Any reference gives the same O / l; the choice only matters for range, and
+  // the caller checks the range afterwards.  No maximum is tracked and nothing is subtracted.
+  // SAFE = true: classic online softmax.  The accumulator of the score MFMA starts at -m_ref so the
+  // MFMA result is already relative to the reference, and m_ref is raised only when a tile exceeds
+  // it by more than 2^kRaise.
+  auto step = [&](auto bufc, auto safec, int it, int J) -> int {
     constexpr int buf = decltype(bufc)::value;
+    constexpr bool SAFE = decltype(safec)::value;
     int J_next = 0;
     if (it + 1 < count) J_next = block_at(it + 1);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile `it` has landed
@@ -227,16 +227,16 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
 
     const unsigned char* tile = smem + buf * BUF_BYTES;
 
-    // ---- S^T = K Q^T - m_ref -----------------------------------------------------------------
-    float base[2];
+    // ---- S^T = K Q^T (- m_ref) ------------------------------------------------------------------
+    float base[2] = {0.f, 0.f};
     f32x16 s[MB][2];
 #pragma unroll
     for (int b2 = 0; b2 < 2; ++b2) {
-      base[b2] = (m_ref[b2] == -INFINITY) ? 0.f : m_ref[b2];
+      if constexpr (SAFE) base[b2] = (m_ref[b2] == -INFINITY) ? 0.f : m_ref[b2];
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s[mb][b2][i] = -base[b2];
+        for (int i = 0; i < 16; ++i) s[mb][b2][i] = SAFE ? -base[b2] : 0.f;
     }
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
@@ -265,27 +265,29 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     bf16x8 pf[2][KC];
 #pragma unroll
     for (int b2 = 0; b2 < 2; ++b2) {
-      float tmax = -INFINITY;
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, s[mb][b2][i]);
-      tmax = fmaxf(tmax, xor32(tmax));
-      const bool unset = m_ref[b2] == -INFINITY;
-      const bool raise = unset ? (tmax > -INFINITY) : (tmax > kRaise);
-      if (__any(raise)) {  // rare after the first tile
-        const float shift = raise ? tmax : 0.f;
-        const float alpha = unset ? 1.f : exp2f(-shift);  // nothing accumulated yet while unset
-        if (raise) m_ref[b2] = base[b2] + shift;
-        l_run[b2] *= alpha;
-#pragma unroll
-        for (int db = 0; db < 2; ++db)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) o[db][b2][i] *= alpha;
+      if constexpr (SAFE) {
+        float tmax = -INFINITY;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) s[mb][b2][i] -= shift;
+          for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, s[mb][b2][i]);
+        tmax = fmaxf(tmax, xor32(tmax));
+        const bool unset = m_ref[b2] == -INFINITY;
+        const bool raise = unset ? (tmax > -INFINITY) : (tmax > kRaise);
+        if (__any(raise)) {  // rare after the first tile
+          const float shift = raise ? tmax : 0.f;
+          const float alpha = unset ? 1.f : exp2f(-shift);  // nothing accumulated yet while unset
+          if (raise) m_ref[b2] = base[b2] + shift;
+          l_run[b2] *= alpha;
+#pragma unroll
+          for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o[db][b2][i] *= alpha;
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s[mb][b2][i] -= shift;
+        }
       }
       const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
       float rowsum = l_run[b2];
@@ -328,66 +330,110 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     return J_next;
   };
 
-  int J0 = 0;
-  if (count > 0) {
-    J0 = block_at(0);
-    issue(J0, 0);
-  }
-  for (int it = 0; it < count; it += 2) {
-    const int J1 = step(std::integral_constant<int, 0>{}, it, J0);
-    if (it + 1 >= count) break;
-    J0 = step(std::integral_constant<int, 1>{}, it + 1, J1);
-  }
-  __syncthreads();  // every wave is done reading the tiles: LDS can be reused
-
-  // ---- merge the two key halves and write ---------------------------------------------------
-  // wave (qi, 1) parks its state in LDS as [qi][68 values][64 lanes]; wave (qi, 0) folds it in.
-  float* park = reinterpret_cast<float*>(smem) + qi * 68 * 64;
-  if (kh == 1) {
+  // A whole pass over the row's key tiles, then the merge of the two key halves: wave (qi, 1)
+  // parks its state in LDS as [qi][68 values][64 lanes] and wave (qi, 0) folds it in.  Returns
+  // true (to every thread of the workgroup) if the pass must be repeated in SAFE mode because a
+  // row sum or an output left the range in which the reference-free weights are trustworthy:
+  // a weight 2^s overflows for s >= 128 (the sum then exceeds the upper limit or O is not finite),
+  // and weights below 2^-126 flush to zero, which is harmless as long as the row sum is at least
+  // 2^-80 (at most 2^24 keys x 2^-126 lost, a relative error under 2^-22 ... 2^-29).
+  auto pass = [&](auto safec) -> bool {
+    constexpr bool SAFE = decltype(safec)::value;
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
       for (int b2 = 0; b2 < 2; ++b2)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) park[((db * 2 + b2) * 16 + i) * 64 + lane] = o[db][b2][i];
-#pragma unroll
-    for (int b2 = 0; b2 < 2; ++b2) {
-      park[(64 + b2) * 64 + lane] = m_ref[b2];
-      park[(66 + b2) * 64 + lane] = l_run[b2];
+        for (int i = 0; i < 16; ++i) o[a][b2][i] = 0.f;
+    m_ref[0] = m_ref[1] = -INFINITY;
+    l_run[0] = l_run[1] = 0.f;
+    idx_cur = load_idx(0);
+    idx_next = load_idx(64);
+    int J0 = 0;
+    if (count > 0) {
+      J0 = block_at(0);
+      issue(J0, 0);
     }
-  }
-  __syncthreads();
-  if (kh == 0) {
+    for (int it = 0; it < count; it += 2) {
+      const int J1 = step(std::integral_constant<int, 0>{}, safec, it, J0);
+      if (it + 1 >= count) break;
+      J0 = step(std::integral_constant<int, 1>{}, safec, it + 1, J1);
+    }
+    __syncthreads();  // every wave is done reading the tiles: LDS can be reused
+
+    float* park = reinterpret_cast<float*>(smem) + qi * 68 * 64;
+    if (kh == 1) {
 #pragma unroll
-    for (int b2 = 0; b2 < 2; ++b2) {
-      const float m1 = park[(64 + b2) * 64 + lane];
-      const float l1 = park[(66 + b2) * 64 + lane];
-      const float m0 = m_ref[b2];
-      const float mt = fmaxf(m0, m1);
-      const float mu = (mt == -INFINITY) ? 0.f : mt;
-      const float a0 = exp2f(m0 - mu), a1 = exp2f(m1 - mu);  // exp2f(-inf) = 0 for a half that saw nothing
-      float lt = l_run[b2] * a0 + l1 * a1;
-      lt += xor32(lt);
-      const float inv = lt > 0.f ? 1.f / lt : 0.f;
-      const int64_t row = int64_t(I) * B + qi * 64 + b2 * 32 + n;
-      if (row < n_tokens) {
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) park[((db * 2 + b2) * 16 + i) * 64 + lane] = o[db][b2][i];
+#pragma unroll
+      for (int b2 = 0; b2 < 2; ++b2) {
+        park[(64 + b2) * 64 + lane] = m_ref[b2];
+        park[(66 + b2) * 64 + lane] = l_run[b2];
+      }
+    }
+    __syncthreads();
+    bool bad = false;
+    float lt[2], mt[2];
+    if (kh == 0) {
+#pragma unroll
+      for (int b2 = 0; b2 < 2; ++b2) {
+        const float l1 = park[(66 + b2) * 64 + lane];
+        float a0 = 1.f, a1 = 1.f;
+        mt[b2] = 0.f;
+        if constexpr (SAFE) {
+          const float m1 = park[(64 + b2) * 64 + lane];
+          const float m0 = m_ref[b2];
+          mt[b2] = fmaxf(m0, m1);
+          const float mu = (mt[b2] == -INFINITY) ? 0.f : mt[b2];
+          a0 = exp2f(m0 - mu);  // exp2f(-inf) = 0 for a half that saw nothing
+          a1 = exp2f(m1 - mu);
+        }
+        float l = l_run[b2] * a0 + l1 * a1;
+        l += xor32(l);
+        lt[b2] = l;
+        if constexpr (!SAFE) bad = bad || !(l >= 0x1p-80f && l <= 0x1p100f);
 #pragma unroll
         for (int db = 0; db < 2; ++db)
 #pragma unroll
-          for (int r4 = 0; r4 < 4; ++r4) {
-            float x[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              const int i = 4 * r4 + r;
-              x[r] = (o[db][b2][i] * a0 + park[((db * 2 + b2) * 16 + i) * 64 + lane] * a1) * inv;
-            }
-            const u32x2 w = {pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3])};
-            *reinterpret_cast<u32x2*>(out + (int64_t(h) * n_tokens + row) * kD + db * 32 + 8 * r4 + 4 * g) = w;
+          for (int i = 0; i < 16; ++i) {
+            o[db][b2][i] = o[db][b2][i] * a0 + park[((db * 2 + b2) * 16 + i) * 64 + lane] * a1;
+            if constexpr (!SAFE) bad = bad || !(fabsf(o[db][b2][i]) < INFINITY);
           }
-        if (lse != nullptr && g == 0)
-          lse[int64_t(h) * n_tokens + row] = lt > 0.f ? (mt + log2f(lt)) * kLn2 : -INFINITY;
       }
     }
+    if constexpr (!SAFE) {
+      if (__syncthreads_or(bad)) return true;
+    }
+    if (kh == 0) {
+#pragma unroll
+      for (int b2 = 0; b2 < 2; ++b2) {
+        const float inv = lt[b2] > 0.f ? 1.f / lt[b2] : 0.f;
+        const int64_t row = int64_t(I) * B + qi * 64 + b2 * 32 + n;
+        if (row < n_tokens) {
+#pragma unroll
+          for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+              const f32x16& x = o[db][b2];
+              const int i = 4 * r4;
+              const u32x2 w = {pack_bf16(x[i] * inv, x[i + 1] * inv), pack_bf16(x[i + 2] * inv, x[i + 3] * inv)};
+              *reinterpret_cast<u32x2*>(out + (int64_t(h) * n_tokens + row) * kD + db * 32 + 8 * r4 + 4 * g) = w;
+            }
+          if (lse != nullptr && g == 0)
+            lse[int64_t(h) * n_tokens + row] = lt[b2] > 0.f ? (mt[b2] + log2f(lt[b2])) * kLn2 : -INFINITY;
+        }
+      }
+    }
+    return false;
+  };
+
+  if (pass(std::false_type{})) {
+    __syncthreads();  // the parked state has been read by everyone: LDS is free for tiles again
+    pass(std::true_type{});
   }
 }
 

@@ -22,6 +22,15 @@ BF16_MAX, BF16_MEAN = 1e-2, 1e-3
 FP32_MAX, FP32_MEAN = 1e-5, 1e-6
 
 
+def _bf16_max_bar(v):
+    """Max-abs bar for the random small-shape cases.  The softmax weights that multiply V are
+    rounded to bf16 (relative error <= 2^-9 each, and the row sum is taken over the rounded
+    weights), so |o_hat - o| <= 2 * 2^-9 * max|v|, plus 2^-9 |o| <= 2^-9 max|v| for rounding the
+    output itself.  The benchmark shapes have max|v| * attention spread small enough for the flat
+    1e-2 bar; a few sharply attended unit-normal values of magnitude 3-4 do not."""
+    return max(BF16_MAX, 1.5 * float(np.abs(v).max()) / 256.0)
+
+
 def _bf16_mean_bar(want):
     """Mean-abs bar for the random small-shape cases.  With a handful of unit-normal keys the
     outputs are O(1) instead of the O(0.1) of the benchmark shapes, and rounding the output
@@ -167,7 +176,7 @@ def test_sparse_attention_small_shapes(B, dtype, b, N):
     torch.cuda.synchronize()
     want, want_lse = O.sparse_attention(q, k, v, mask, b, return_lse=True)
     mx, mean = attn_errors(out, want)
-    lim = (BF16_MAX, _bf16_mean_bar(want)) if dtype == "bf16" else (FP32_MAX, FP32_MEAN)
+    lim = (_bf16_max_bar(v), _bf16_mean_bar(want)) if dtype == "bf16" else (FP32_MAX, FP32_MEAN)
     assert mx <= lim[0] and mean <= lim[1], (mx, mean)
     assert np.abs(lse.cpu().numpy() - want_lse).max() <= (2e-2 if dtype == "bf16" else 1e-5)
 
@@ -180,7 +189,7 @@ def test_dense_attention_small_shapes(B, dtype, N):
     torch.cuda.synchronize()
     want, want_lse = O.dense_attention(q, k, v, return_lse=True)
     mx, mean = attn_errors(out, want)
-    lim = (BF16_MAX, _bf16_mean_bar(want)) if dtype == "bf16" else (FP32_MAX, FP32_MEAN)
+    lim = (_bf16_max_bar(v), _bf16_mean_bar(want)) if dtype == "bf16" else (FP32_MAX, FP32_MEAN)
     assert mx <= lim[0] and mean <= lim[1], (mx, mean)
     assert np.abs(lse.cpu().numpy() - want_lse).max() <= (2e-2 if dtype == "bf16" else 1e-5)
 
