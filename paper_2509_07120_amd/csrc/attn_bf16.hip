@@ -29,6 +29,9 @@
 // 2^8 (the weights then stay <= 256, harmless in fp32/bf16); the final O / l is exact for any
 // reference, so this only skips rescaling work.  Row sums are taken from the bf16-rounded
 // weights (dot2 with ones), i.e. from exactly what multiplies V.
+#include <stdio.h>
+#include <stdlib.h>
+
 #include <type_traits>
 
 #include "bsga_internal.h"
@@ -62,12 +65,32 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
 
 __device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32); }
 
-// 16 bytes per lane from a raw buffer straight into LDS: lane i's data lands at lds_dst + 16 i.
-// voff is the per-lane byte offset, soff a wave-uniform one; reads past the buffer's size return 0.
-__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t rsrc, unsigned voff, unsigned soff,
-                                      unsigned char* lds_dst) {
-  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(lds_dst), 16, voff, soff,
-                                           0, 0);
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// 16 bytes per lane from a raw buffer straight into LDS (buffer_load_dwordx4 ... lds): lane i's
+// data lands at LDS byte address lds_addr + 16 i.  voff is the per-lane byte offset, soff a
+// wave-uniform one; reads past the buffer's size return 0.  Written as inline assembly on purpose:
+// the compiler then does not count these loads as LDS writes and so does not make later LDS reads
+// of the *other* buffer wait for them; the kernel orders them itself (s_waitcnt vmcnt + barrier).
+__device__ __forceinline__ void dma16(i32x4 rsrc, unsigned voff, unsigned soff, unsigned lds_addr) {
+  unsigned saved_m0;  // M0 (the LDS base of the load) is put back, so the statement has no side effect on it
+  asm volatile(
+      "s_mov_b32 %0, m0\n\t"
+      "s_mov_b32 m0, %1\n\t"
+      "buffer_load_dwordx4 %2, %3, %4 offen lds\n\t"
+      "s_mov_b32 m0, %0"
+      : "=&s"(saved_m0)
+      : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+      : "memory");
+}
+
+// raw buffer descriptor over [base, base + bytes): stride 0, 32-bit element data format
+__device__ __forceinline__ i32x4 make_rsrc(const void* base, unsigned bytes) {
+  const unsigned long long a = reinterpret_cast<unsigned long long>(base);
+  const i32x4 r = {__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<unsigned>(a))),
+                   __builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<unsigned>(a >> 32) & 0xffffu)),
+                   __builtin_amdgcn_readfirstlane(static_cast<int>(bytes)), 0x00020000};
+  return r;
 }
 
 template <int B>
@@ -97,10 +120,10 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   const int64_t rowid = int64_t(h) * nb + I;
   // raw buffer views of this head's K and V (byte-addressed, bounds-checked by the hardware)
   const unsigned head_size = static_cast<unsigned>(n_tokens * 128);
-  const __amdgpu_buffer_rsrc_t krsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(k + head_bytes), 0, head_size, 0x00020000);
-  const __amdgpu_buffer_rsrc_t vrsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(v + head_bytes), 0, head_size, 0x00020000);
+  const i32x4 krsrc = make_rsrc(k + head_bytes, head_size);
+  const i32x4 vrsrc = make_rsrc(v + head_bytes, head_size);
+  const unsigned smem_addr =
+      static_cast<unsigned>(reinterpret_cast<size_t>((__attribute__((address_space(3))) unsigned char*)smem));
 
   // ---- Q fragments (B operand of S^T = K Q^T), pre-scaled: lane (n, g) holds dims 16c + 8g .. +7
   bf16x8 qf[2][4];
@@ -186,29 +209,42 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     const int J = __builtin_amdgcn_readlane(idx_cur, it & 63);
     return min(max(J, 0), nb - 1);
   };
-  // enqueue the direct-to-LDS loads of key tile J into buffer `buf`
-  auto issue = [&](int J, int buf) {
+  // Direct-to-LDS load number i (0..7) of key tile J into buffer `buf`: even i moves 1 KB of the K
+  // tile, odd i 1 KB of the V tile.  The eight loads of a tile are issued one at a time between
+  // MFMAs so that they never queue up in front of the LDS reads.  Rows of a ragged last tile that
+  // lie past the end of the head's buffer are out of range for the hardware bounds check, which
+  // makes the load write zeros for them.
+  auto issue_part = [&](int J, int buf, int i2) {
+    const int i = i2 >> 1;
+    const bool is_v = (i2 & 1) != 0;
     const unsigned soff = static_cast<unsigned>(J) * TILE_BYTES;
-    unsigned char* dst = smem + buf * BUF_BYTES + wave * 1024;
-    if (J == nb - 1 && tail < B) {  // ragged tile: rows past the end re-read the last valid row
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int r = dma_r0 + 8 * NW * i;
-        const int rs = min(r, tail - 1);
-        dma16(krsrc, rs * 128 + ((dma_pc ^ swz_k(r)) << 4), soff, dst + NW * i * 1024);
-        dma16(vrsrc, rs * 128 + ((dma_pc ^ swz_v(r)) << 4), soff, dst + TILE_BYTES + NW * i * 1024);
-      }
+    const unsigned dst = smem_addr + buf * BUF_BYTES + wave * 1024 + (is_v ? TILE_BYTES : 0) + NW * i * 1024;
+    if (is_v) {
+      dma16(vrsrc, voff, soff + i * NW * 1024, dst);
     } else {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        dma16(krsrc, koff[i % KN], soff + (i / KN) * KN * NW * 1024, dst + NW * i * 1024);
-        dma16(vrsrc, voff, soff + i * NW * 1024, dst + TILE_BYTES + NW * i * 1024);
-      }
+      dma16(krsrc, koff[i % KN], soff + (i / KN) * KN * NW * 1024, dst);
     }
   };
+  auto issue = [&](int J, int buf) {
+#pragma unroll
+    for (int i2 = 0; i2 < 8; ++i2) issue_part(J, buf, i2);
+  };
 
-  // One key tile: wait for its loads, start the next tile's loads, compute.  BUF is a compile-time
-  // constant so every LDS address below is a lane-constant register plus an immediate.
+  // K operands (A of S^T = K Q^T) of 32-key sub-tile mb from the tile in buffer `buf`.  Chunk c of
+  // sub-tile 1 sits where chunk c ^ 2 of sub-tile 0 does (swz_k(r + 32) = swz_k(r) ^ 4).
+  bf16x8 ka[4];
+  auto read_k = [&](int buf, int mb) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      ka[c] = *LDS_PTR(bf16x8, smem + buf * BUF_BYTES + kaddr[(mb & 1) ? (c ^ 2) : c] + mb * 4096);
+  };
+
+  // One key tile, software pipelined against its neighbours.  On entry the tile's data is in
+  // buffer BUF, visible to every wave, and ka holds the K operands of its first sub-tile.  Per
+  // 32-key sub-tile: scores (8 MFMAs) -> weights (VALU) -> O update (8 MFMAs).  Before the last O
+  // update the workgroup synchronises: from then on nobody reads buffer BUF any more, so the loads
+  // of tile it+2 are started into it, and tile it+1 (in the other buffer) is known to have landed,
+  // so its first K operands are fetched while the last 8 MFMAs run.
   //
   // SAFE = false (fast pass): weights are exp2 of the raw scaled logits, i.e. the softmax reference
   // is 0 for every row.  Any reference gives the same O / l; the choice only matters for range, and
@@ -216,118 +252,128 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   // SAFE = true: classic online softmax.  The accumulator of the score MFMA starts at -m_ref so the
   // MFMA result is already relative to the reference, and m_ref is raised only when a tile exceeds
   // it by more than 2^kRaise.
-  auto step = [&](auto bufc, auto safec, int it, int J) -> int {
+  auto step = [&](auto bufc, auto safec, int it, bool ragged, int J_next2) {
     constexpr int buf = decltype(bufc)::value;
     constexpr bool SAFE = decltype(safec)::value;
-    int J_next = 0;
-    if (it + 1 < count) J_next = block_at(it + 1);
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile `it` has landed
-    __syncthreads();                     // ... and so has everyone else's; buffer buf^1 is free
-    if (it + 1 < count) issue(J_next, buf ^ 1);
-
     const unsigned char* tile = smem + buf * BUF_BYTES;
 
-    // ---- S^T = K Q^T (- m_ref) ------------------------------------------------------------------
-    float base[2] = {0.f, 0.f};
-    f32x16 s[MB][2];
-#pragma unroll
-    for (int b2 = 0; b2 < 2; ++b2) {
-      if constexpr (SAFE) base[b2] = (m_ref[b2] == -INFINITY) ? 0.f : m_ref[b2];
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s[mb][b2][i] = SAFE ? -base[b2] : 0.f;
-    }
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
+      const bool last = (mb == MB - 1);
+      // V^T operands of this sub-tile: [dim block][16-key chunk] = two 4-key transpose reads each
+      bf16x8 va[2][2];
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const bf16x8 a = *LDS_PTR(bf16x8, tile + kaddr[mb ? (c ^ 2) : c] + mb * 4096);
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int cp = 0; cp < 2; ++cp) {
+          const int key0 = (2 * mb + cp) * 16;
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (s16x4 __attribute__((address_space(3)))*)(tile + vaddr[db] + key0 * 128));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (s16x4 __attribute__((address_space(3)))*)(tile + vaddr[db] + (key0 + 8) * 128));
+          const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
+          const u32x4 av = {lo2[0], lo2[1], hi2[0], hi2[1]};
+          va[db][cp] = __builtin_bit_cast(bf16x8, av);
+        }
+
+      // ---- S^T = K Q^T (- m_ref) for 32 keys x 64 queries ------------------------------------------
+      float base[2] = {0.f, 0.f};
+      f32x16 sc[2];
+#pragma unroll
+      for (int b2 = 0; b2 < 2; ++b2) {
+        if constexpr (SAFE) base[b2] = (m_ref[b2] == -INFINITY) ? 0.f : m_ref[b2];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sc[b2][i] = SAFE ? -base[b2] : 0.f;
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
 #pragma unroll
         for (int b2 = 0; b2 < 2; ++b2)
-          s[mb][b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[b2][c], s[mb][b2], 0, 0, 0);
-      }
-    }
-    if (J == nb - 1 && tail < B) {  // ragged last key block: keys past the end get -inf
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int key = kh * KW + mb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-          if (key >= tail) {
-            s[mb][0][i] = -INFINITY;
-            s[mb][1][i] = -INFINITY;
-          }
-        }
-    }
-
-    // ---- softmax weights, per query column -------------------------------------------------------
-    bf16x8 pf[2][KC];
-#pragma unroll
-    for (int b2 = 0; b2 < 2; ++b2) {
+          sc[b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c], qf[b2][c], sc[b2], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (!last) read_k(buf, mb + 1);  // lands while the weights below are computed
       if constexpr (SAFE) {
-        float tmax = -INFINITY;
+        // Ragged last key block: its rows past the end were loaded as zeros (score 0, value 0).
+        // The running-max form masks them out; the fast pass instead lets each contribute a weight
+        // of exactly 2^0 = 1 to the row sum and nothing to O, and subtracts their count at the end.
+        if (ragged) {
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, s[mb][b2][i]);
-        tmax = fmaxf(tmax, xor32(tmax));
-        const bool unset = m_ref[b2] == -INFINITY;
-        const bool raise = unset ? (tmax > -INFINITY) : (tmax > kRaise);
-        if (__any(raise)) {  // rare after the first tile
-          const float shift = raise ? tmax : 0.f;
-          const float alpha = unset ? 1.f : exp2f(-shift);  // nothing accumulated yet while unset
-          if (raise) m_ref[b2] = base[b2] + shift;
-          l_run[b2] *= alpha;
-#pragma unroll
-          for (int db = 0; db < 2; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[db][b2][i] *= alpha;
-#pragma unroll
-          for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) s[mb][b2][i] -= shift;
+          for (int i = 0; i < 16; ++i) {
+            const int key = kh * KW + mb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
+            if (key >= tail) {
+              sc[0][i] = -INFINITY;
+              sc[1][i] = -INFINITY;
+            }
+          }
         }
       }
-      const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
-      float rowsum = l_run[b2];
-#pragma unroll
-      for (int kc = 0; kc < KC; ++kc) {
-        const int mb = kc >> 1, cp = kc & 1;
-        u32x4 w;
-#pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-          for (int r2 = 0; r2 < 2; ++r2) {
-            const int i0 = 4 * (2 * cp + t2) + 2 * r2;
-            const unsigned pk =
-                pack_bf16(__builtin_amdgcn_exp2f(s[mb][b2][i0]), __builtin_amdgcn_exp2f(s[mb][b2][i0 + 1]));
-            rowsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, rowsum, false);
-            w[2 * t2 + r2] = pk;
-          }
-        pf[b2][kc] = __builtin_bit_cast(bf16x8, w);
-      }
-      l_run[b2] = rowsum;
-    }
 
-    // ---- O^T += V^T P^T -----------------------------------------------------------------------
+      // ---- softmax weights, per query column -----------------------------------------------------
+      bf16x8 pf[2][2];
 #pragma unroll
-    for (int db = 0; db < 2; ++db) {
+      for (int b2 = 0; b2 < 2; ++b2) {
+        if constexpr (SAFE) {
+          float tmax = -INFINITY;
 #pragma unroll
-      for (int kc = 0; kc < KC; ++kc) {
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (s16x4 __attribute__((address_space(3)))*)(tile + vaddr[db] + (kc * 16) * 128));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (s16x4 __attribute__((address_space(3)))*)(tile + vaddr[db] + (kc * 16 + 8) * 128));
-        const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
-        const u32x4 av = {lo2[0], lo2[1], hi2[0], hi2[1]};
-        const bf16x8 a = __builtin_bit_cast(bf16x8, av);
+          for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sc[b2][i]);
+          tmax = fmaxf(tmax, xor32(tmax));
+          const bool unset = m_ref[b2] == -INFINITY;
+          const bool raise = unset ? (tmax > -INFINITY) : (tmax > kRaise);
+          if (__any(raise)) {  // rare after the first tile
+            const float shift = raise ? tmax : 0.f;
+            const float alpha = unset ? 1.f : exp2f(-shift);  // nothing accumulated yet while unset
+            if (raise) m_ref[b2] = base[b2] + shift;
+            l_run[b2] *= alpha;
 #pragma unroll
-        for (int b2 = 0; b2 < 2; ++b2)
-          o[db][b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[b2][kc], o[db][b2], 0, 0, 0);
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+              for (int i = 0; i < 16; ++i) o[db][b2][i] *= alpha;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sc[b2][i] -= shift;
+          }
+        }
+        const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
+        float rowsum = l_run[b2];
+#pragma unroll
+        for (int cp = 0; cp < 2; ++cp) {
+          u32x4 w;
+#pragma unroll
+          for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+            for (int r2 = 0; r2 < 2; ++r2) {
+              const int i0 = 4 * (2 * cp + t2) + 2 * r2;
+              const unsigned pk = pack_bf16(__builtin_amdgcn_exp2f(sc[b2][i0]), __builtin_amdgcn_exp2f(sc[b2][i0 + 1]));
+              rowsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, rowsum, false);
+              w[2 * t2 + r2] = pk;
+            }
+          pf[b2][cp] = __builtin_bit_cast(bf16x8, w);
+        }
+        l_run[b2] = rowsum;
       }
+      __builtin_amdgcn_sched_barrier(0);
+
+      if (last) {
+        // every LDS read of this tile has been issued; once all waves are here the buffer is free
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile it+1 has landed
+        __syncthreads();
+        if (it + 1 < count) read_k(buf ^ 1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+
+      // ---- O^T += V^T P^T, with the loads of tile it+2 slotted between the last MFMAs -------------
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int cp = 0; cp < 2; ++cp)
+#pragma unroll
+          for (int b2 = 0; b2 < 2; ++b2) {
+            o[db][b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db][cp], pf[b2][cp], o[db][b2], 0, 0, 0);
+            if (last) {
+              if (it + 2 < count) issue_part(J_next2, buf, (db * 2 + cp) * 2 + b2);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
     }
-    return J_next;
   };
 
   // A whole pass over the row's key tiles, then the merge of the two key halves: wave (qi, 1)
@@ -349,15 +395,31 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     l_run[0] = l_run[1] = 0.f;
     idx_cur = load_idx(0);
     idx_next = load_idx(64);
-    int J0 = 0;
+    // prologue: tile 0 -> buffer 0, wait for it, tile 1 -> buffer 1, first K operands
+    int J_cur = 0, J_nxt = 0;
     if (count > 0) {
-      J0 = block_at(0);
-      issue(J0, 0);
+      J_cur = block_at(0);
+      issue(J_cur, 0);
+      if (count > 1) J_nxt = block_at(1);
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      __syncthreads();
+      if (count > 1) issue(J_nxt, 1);
+      read_k(0, 0);
     }
+    int pad_keys = 0;  // zero-filled keys past the end that the fast pass has summed as weight 1
+    auto tile_step = [&](auto bufc, int it, int J, int J_next2) {
+      const bool ragged = (J == nb - 1 && tail < B);
+      if (ragged) pad_keys += B - tail;
+      step(bufc, safec, it, ragged, J_next2);
+    };
     for (int it = 0; it < count; it += 2) {
-      const int J1 = step(std::integral_constant<int, 0>{}, safec, it, J0);
+      int J2 = (it + 2 < count) ? block_at(it + 2) : 0;
+      tile_step(std::integral_constant<int, 0>{}, it, J_cur, J2);
       if (it + 1 >= count) break;
-      J0 = step(std::integral_constant<int, 1>{}, safec, it + 1, J1);
+      const int J3 = (it + 3 < count) ? block_at(it + 3) : 0;
+      tile_step(std::integral_constant<int, 1>{}, it + 1, J_nxt, J3);
+      J_cur = J2;
+      J_nxt = J3;
     }
     __syncthreads();  // every wave is done reading the tiles: LDS can be reused
 
@@ -394,6 +456,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
         }
         float l = l_run[b2] * a0 + l1 * a1;
         l += xor32(l);
+        if constexpr (!SAFE) l -= static_cast<float>(pad_keys);
         lt[b2] = l;
         if constexpr (!SAFE) bad = bad || !(l >= 0x1p-80f && l <= 0x1p100f);
 #pragma unroll
@@ -450,6 +513,12 @@ int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int
   const unsigned char* kp = static_cast<const unsigned char*>(k);
   const unsigned char* vp = static_cast<const unsigned char*>(v);
   unsigned short* op = static_cast<unsigned short*>(out);
+  if (getenv("BSGA_DEBUG") != nullptr) {
+    int n64 = -1, n128 = -1;
+    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n64, attn_bf16_kernel<64>, 128, 4 * 64 * 128);
+    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n128, attn_bf16_kernel<128>, 256, 4 * 128 * 128);
+    fprintf(stderr, "[bsga] attention occupancy (workgroups per CU): block 64 -> %d, block 128 -> %d\n", n64, n128);
+  }
   if (block == 64) {
     hipLaunchKernelGGL((attn_bf16_kernel<64>), grid, dim3(128), 4 * 64 * 128, stream, qp, kp, vp, op, lse, kv_idx,
                        kv_cnt, idx_stride, n_tokens, nb, scale_log2);

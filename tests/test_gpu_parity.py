@@ -194,6 +194,37 @@ def test_dense_attention_small_shapes(B, dtype, N):
     assert np.abs(lse.cpu().numpy() - want_lse).max() <= (2e-2 if dtype == "bf16" else 1e-5)
 
 
+@pytest.mark.parametrize("sign", [+1.0, -1.0])
+def test_out_of_range_logits_fall_back_to_online_softmax(B, sign):
+    """The bf16 kernel first runs with softmax reference 0 and repeats a workgroup with the
+    running-max form when a row sum leaves [2^-80, 2^100].  A common component of 27 along one unit
+    direction puts every logit near +-91 nats (+-131 in log2 units), which overflows (+) or flushes
+    to zero (-) in the first pass.  Logits this large also amplify the bf16 rounding of the
+    pre-scaled Q (relative 2^-9 of a 131-magnitude exponent is ~0.02), hence the wider bars."""
+    H, N, b = 2, 600, 128
+    rng = np.random.default_rng(11)
+    u = np.full(64, 1.0 / 8.0, dtype=np.float32)
+    from workload import bf16_bits_to_f32, round_to_bf16_bits
+    q = bf16_bits_to_f32(round_to_bf16_bits(rng.standard_normal((H, N, 64)).astype(np.float32) + 27.0 * u))
+    k = bf16_bits_to_f32(round_to_bf16_bits(rng.standard_normal((H, N, 64)).astype(np.float32) + sign * 27.0 * u))
+    v = bf16_bits_to_f32(round_to_bf16_bits(rng.standard_normal((H, N, 64)).astype(np.float32)))
+    nb = O.num_blocks(N, b)
+    mask = _random_mask(H, nb, 0.6, 3)
+    idx, cnt = _lists(mask)
+    tq, tk, tv = (to_device(x, "bf16") for x in (q, k, v))
+    out, lse = B.bsga_sparse_attn(tq, tk, tv, b, idx, cnt, return_lse=True)
+    dense, dlse = B.bsga_dense_attn(tq, tk, tv, return_lse=True)
+    torch.cuda.synchronize()
+    want, want_lse = O.sparse_attention(q, k, v, mask, b, return_lse=True)
+    assert abs(np.median(want_lse)) > 80.0  # the case really is out of the fast pass's range
+    for got, got_lse, ref, ref_lse in ((out, lse, want, want_lse),
+                                       (dense, dlse) + O.dense_attention(q, k, v, return_lse=True)):
+        assert torch.isfinite(got.float()).all()
+        mx, mean = attn_errors(got, ref)
+        assert mx <= 5e-2 and mean <= 5e-3, (mx, mean)
+        assert np.abs(got_lse.cpu().numpy() - ref_lse).max() <= 0.25
+
+
 def test_empty_row_yields_zeros(B):
     H, N, b = 1, 256, 128
     q, k, v = _rand_qkv(H, N, 5, "bf16")
