@@ -1,34 +1,33 @@
 // bf16 flash-style attention over kept key blocks for gfx950 (Sec. 4.1, Eq. (2); Eq. (1) when no
-// index list is given).  bf16 MFMA (32x32x16) for both products, fp32 accumulation, fp32 online
-// softmax in the log2 domain.
+// index list is given).  bf16 MFMA (32x32x16) for both products, fp32 accumulation, fp32 softmax
+// weights in the log2 domain.
 //
 // Work split.  One workgroup per (head, query block of B rows); it walks the row's kept key
-// blocks (tiles of B keys).  Waves are arranged WQ x 2: wave (qi, kh) owns 64 query rows (qi)
-// and one half of every key tile (kh), so each K/V operand fetched from LDS feeds two MFMAs.
-// The two key halves keep independent softmax states that are merged once at the end.  Two
-// workgroups share a CU (two waves per SIMD), so one wave's softmax VALU work overlaps the
-// other's MFMAs.
+// blocks (tiles of B keys).  Each of the B/32 waves owns 32 query rows and sees every key of a
+// tile, so a wave's softmax state is private and nothing is merged at the end.  Two workgroups
+// share a CU (two waves per SIMD).
 //
 // Data movement.  K and V tiles go HBM/L2 -> LDS with direct-to-LDS loads (16 bytes per lane, no
-// staging registers), double buffered: the loads of tile t+1 are in flight while tile t is
-// computed.  Tiles stay row-major [key][64]; only the order of the eight 16-byte chunks inside a
-// row is permuted (XOR swizzle, chosen per tensor) so the operand reads below are conflict free.
+// staging registers), double buffered.  Tiles stay row-major [key][64]; only the order of the eight
+// 16-byte chunks inside a row is permuted (XOR swizzle, chosen per tensor) so the operand reads
+// below are bank-conflict free.  gfx950's LDS delivers ~250 B/clk per CU for 16-byte reads, which
+// is what lets every wave read the whole tile.
 //
 // Register layouts.  Scores are produced transposed, S^T = K Q^T (M = keys, N = queries): in the
 // 32x32 accumulator layout lane (n = lane%32, g = lane/32) holds, for query n, the keys
-// 8*r4 + 4*g + r (register 4*r4 + r).  A lane owns whole query columns, so row max/sum need one
-// cross-lane step (lane ^ 32), and after exponentiation the same registers are, with no data
-// movement, the B operand of O^T += V^T P^T if the contraction index is taken in the order the
-// accumulator holds the keys.  The matching A operand (V^T: 32 dims x 16 keys) is read from the
-// row-major V tile with the LDS transpose read (ds_read_b64_tr_b16): each 16-lane group names four
-// keys and gets, per lane, those four keys' values of one dim.
+// 8*r4 + 4*g + r (register 4*r4 + r).  A lane owns a whole query column, so row sums need one
+// cross-lane step (lane ^ 32) at the very end, and after exponentiation the same registers are,
+// with no data movement, the B operand of O^T += V^T P^T if the contraction index is taken in the
+// order the accumulator holds the keys.  The matching A operand (V^T: 32 dims x 16 keys) is read
+// from the row-major V tile with the LDS transpose read (ds_read_b64_tr_b16): each 16-lane group
+// names four keys and gets, per lane, those four keys' values of one dim.
 //
-// Softmax.  Q is pre-multiplied by softmax_scale*log2(e) when it is loaded, and the accumulator
-// of the score MFMA is initialised to -m_ref (the lane's reference maximum), so the MFMA result
-// is already the exponent of exp2.  m_ref is raised only when a tile exceeds it by more than
-// 2^8 (the weights then stay <= 256, harmless in fp32/bf16); the final O / l is exact for any
-// reference, so this only skips rescaling work.  Row sums are taken from the bf16-rounded
-// weights (dot2 with ones), i.e. from exactly what multiplies V.
+// Softmax.  Q is pre-multiplied by softmax_scale*log2(e) when it is loaded.  The fast pass takes
+// the weights as exp2 of the raw scaled logits, i.e. with reference 0 for every row: any reference
+// gives the same O / l, the choice only matters for range, and the range is checked afterwards
+// (see pass()).  Only if that check fails is the workgroup repeated with a running reference
+// maximum (SAFE pass).  Row sums are taken from the bf16-rounded weights (dot2 with ones), i.e.
+// from exactly what multiplies V.
 #include <stdio.h>
 #include <stdlib.h>
 
@@ -46,13 +45,17 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 #define LDS_PTR(T, p) ((const T __attribute__((address_space(3)))*)(p))
 
 constexpr int kD = 64;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kRaise = 8.0f;  // raise the reference maximum when a tile exceeds it by 2^8
+constexpr float kRaise = 8.0f;  // SAFE pass: raise the reference maximum when a tile exceeds it by 2^8
+
+template <int V>
+using Int = std::integral_constant<int, V>;
 
 // chunk swizzles: 16-byte chunk c of tile row r is stored at chunk position c ^ swz(r)
 __device__ __forceinline__ int swz_k(int row) { return (row ^ (row >> 3)) & 7; }
@@ -65,15 +68,14 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
 
 __device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32); }
 
-typedef int i32x4 __attribute__((ext_vector_type(4)));
-
 // 16 bytes per lane from a raw buffer straight into LDS (buffer_load_dwordx4 ... lds): lane i's
 // data lands at LDS byte address lds_addr + 16 i.  voff is the per-lane byte offset, soff a
-// wave-uniform one; reads past the buffer's size return 0.  Written as inline assembly on purpose:
-// the compiler then does not count these loads as LDS writes and so does not make later LDS reads
-// of the *other* buffer wait for them; the kernel orders them itself (s_waitcnt vmcnt + barrier).
+// wave-uniform one; lanes whose offset is past the buffer's size get zeros.  Written as inline
+// assembly on purpose: the compiler then does not count these loads as LDS writes and so does not
+// make later LDS reads of the *other* buffer wait for them; the kernel orders them itself
+// (s_waitcnt vmcnt + barrier).  M0 (the LDS base of the load) is put back afterwards.
 __device__ __forceinline__ void dma16(i32x4 rsrc, unsigned voff, unsigned soff, unsigned lds_addr) {
-  unsigned saved_m0;  // M0 (the LDS base of the load) is put back, so the statement has no side effect on it
+  unsigned saved_m0;
   asm volatile(
       "s_mov_b32 %0, m0\n\t"
       "s_mov_b32 m0, %1\n\t"
@@ -98,11 +100,8 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     const unsigned char* __restrict__ q, const unsigned char* __restrict__ k, const unsigned char* __restrict__ v,
     unsigned short* __restrict__ out, float* __restrict__ lse, const int32_t* __restrict__ kv_idx,
     const int32_t* __restrict__ kv_cnt, int idx_stride, int64_t n_tokens, int nb, float scale_log2) {
-  constexpr int WQ = B / 64;              // waves along queries
-  constexpr int KW = B / 2;               // keys per wave per tile
-  constexpr int MB = KW / 32;             // 32-key MFMA row blocks per wave
-  constexpr int KC = KW / 16;             // 16-key contraction chunks per wave in P V
-  constexpr int NW = B / 32;              // waves per workgroup
+  constexpr int NW = B / 32;              // waves per workgroup (2 B threads), 32 query rows each
+  constexpr int NU = B / 32;              // 32-key sub-tiles ("units") per key tile
   constexpr int TILE_BYTES = B * 128;     // one K or V tile
   constexpr int BUF_BYTES = 2 * TILE_BYTES;
   extern __shared__ __align__(1024) unsigned char smem[];  // [2 buffers][K tile | V tile]
@@ -112,8 +111,6 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   const int lane = tid & 63;
   const int n = lane & 31;
   const int g = lane >> 5;
-  const int qi = wave % WQ;
-  const int kh = wave / WQ;
   const int I = blockIdx.x;
   const int h = blockIdx.y;
   const int64_t head_bytes = int64_t(h) * n_tokens * 128;
@@ -126,23 +123,20 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
       static_cast<unsigned>(reinterpret_cast<size_t>((__attribute__((address_space(3))) unsigned char*)smem));
 
   // ---- Q fragments (B operand of S^T = K Q^T), pre-scaled: lane (n, g) holds dims 16c + 8g .. +7
-  bf16x8 qf[2][4];
+  const int64_t qrow = int64_t(I) * B + wave * 32 + n;
+  bf16x8 qf[4];
 #pragma unroll
-  for (int b2 = 0; b2 < 2; ++b2) {
-    const int64_t row = int64_t(I) * B + qi * 64 + b2 * 32 + n;
+  for (int c = 0; c < 4; ++c) {
+    u32x4 x = {0u, 0u, 0u, 0u};
+    if (qrow < n_tokens) x = *reinterpret_cast<const u32x4*>(q + head_bytes + qrow * 128 + (2 * c + g) * 16);
+    u32x4 y;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      u32x4 x = {0u, 0u, 0u, 0u};
-      if (row < n_tokens) x = *reinterpret_cast<const u32x4*>(q + head_bytes + row * 128 + (2 * c + g) * 16);
-      u32x4 y;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float lo = __uint_as_float(x[e] << 16) * scale_log2;
-        const float hi = __uint_as_float(x[e] & 0xffff0000u) * scale_log2;
-        y[e] = pack_bf16(lo, hi);
-      }
-      qf[b2][c] = __builtin_bit_cast(bf16x8, y);
+    for (int e = 0; e < 4; ++e) {
+      const float lo = __uint_as_float(x[e] << 16) * scale_log2;
+      const float hi = __uint_as_float(x[e] & 0xffff0000u) * scale_log2;
+      y[e] = pack_bf16(lo, hi);
     }
+    qf[c] = __builtin_bit_cast(bf16x8, y);
   }
 
   // ---- per-lane constants -------------------------------------------------------------------------
@@ -162,21 +156,18 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     koff[i] = r * 128 + ((dma_pc ^ swz_k(r)) << 4);
   }
   const unsigned voff = dma_r0 * 128 + ((dma_pc ^ swz_v(dma_r0)) << 4);
-  // K operand reads (ds_read_b128): row r = kh*KW + mb*32 + n, logical chunk 2c + g.  Since
-  // swz_k(r + 32) = swz_k(r) ^ 4, block mb = 1 reads chunk c where block 0 reads chunk c ^ 2.
+  // K operand reads (ds_read_b128) of sub-tile u: row r = 32u + n, logical chunk 2c + g.  Since
+  // swz_k(r + 32) = swz_k(r) ^ 4, an odd sub-tile reads chunk c where an even one reads chunk c ^ 2.
   unsigned kaddr[4];
-  {
-    const int r = kh * KW + n;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) kaddr[c] = r * 128 + (((2 * c + g) ^ swz_k(r)) << 4);
-  }
+  for (int c = 0; c < 4; ++c) kaddr[c] = n * 128 + (((2 * c + g) ^ swz_k(n)) << 4);
   // V operand reads (transpose read, 8 bytes per lane): 16-lane group G = lane/16 covers dims
   // db*32 + 16*(G&1) .. +15 for key-slot half g = G/2; inside the group lane i names key
-  // m = i/4 of the four and the dim quad j = i%4.
+  // m = i/4 of the four and the dim quad j = i%4.  Key = 32u + 16cp + 8t + 4g + m.
   unsigned vaddr[2];
   {
     const int i16 = lane & 15, m = i16 >> 2, j = i16 & 3, G = lane >> 4;
-    const int keyl = kh * KW + 4 * g + m;  // + 16*kc + 8*t added as an immediate
+    const int keyl = 4 * g + m;
 #pragma unroll
     for (int db = 0; db < 2; ++db) {
       const int cc = db * 4 + 2 * (G & 1) + (j >> 1);
@@ -184,9 +175,9 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     }
   }
 
-  f32x16 o[2][2];
-  float m_ref[2];  // reference maximum per query column (log2 domain); unused by the fast pass
-  float l_run[2];  // this lane's share of the row sum
+  f32x16 o[2];     // O^T accumulators: [dim block], this lane's query column
+  float m_ref;     // SAFE pass: reference maximum of the query column (log2 domain)
+  float l_run;     // this lane's share of the row sum
 
   const bool dense = kv_idx == nullptr;
   const int count = dense ? nb : min(max(kv_cnt[rowid], 0), nb);
@@ -209,11 +200,9 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     const int J = __builtin_amdgcn_readlane(idx_cur, it & 63);
     return min(max(J, 0), nb - 1);
   };
-  // Direct-to-LDS load number i (0..7) of key tile J into buffer `buf`: even i moves 1 KB of the K
-  // tile, odd i 1 KB of the V tile.  The eight loads of a tile are issued one at a time between
-  // MFMAs so that they never queue up in front of the LDS reads.  Rows of a ragged last tile that
-  // lie past the end of the head's buffer are out of range for the hardware bounds check, which
-  // makes the load write zeros for them.
+  // Direct-to-LDS load number i2 (0..7) of key tile J into buffer `buf`: even i2 moves 1 KB of the
+  // K tile, odd i2 1 KB of the V tile.  Rows of a ragged last tile that lie past the end of the
+  // head's buffer fail the hardware bounds check, which makes the load write zeros for them.
   auto issue_part = [&](int J, int buf, int i2) {
     const int i = i2 >> 1;
     const bool is_v = (i2 & 1) != 0;
@@ -230,272 +219,295 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     for (int i2 = 0; i2 < 8; ++i2) issue_part(J, buf, i2);
   };
 
-  // K operands (A of S^T = K Q^T) of 32-key sub-tile mb from the tile in buffer `buf`.  Chunk c of
-  // sub-tile 1 sits where chunk c ^ 2 of sub-tile 0 does (swz_k(r + 32) = swz_k(r) ^ 4).
-  bf16x8 ka[4];
-  auto read_k = [&](int buf, int mb) {
+  // K operands (A of S^T = K Q^T) of 32-key sub-tile u of the tile in buffer `buf`
+  auto read_k = [&](bf16x8 (&ka)[4], int buf, int u) {
 #pragma unroll
     for (int c = 0; c < 4; ++c)
-      ka[c] = *LDS_PTR(bf16x8, smem + buf * BUF_BYTES + kaddr[(mb & 1) ? (c ^ 2) : c] + mb * 4096);
+      ka[c] = *LDS_PTR(bf16x8, smem + buf * BUF_BYTES + kaddr[(u & 1) ? (c ^ 2) : c] + u * 4096);
+  };
+  // V^T operands (A of O^T += V^T P^T) of sub-tile u: [dim block][16-key chunk]
+  auto read_v = [&](bf16x8 (&va)[2][2], int buf, int u) {
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int cp = 0; cp < 2; ++cp) {
+        const unsigned char* p = smem + buf * BUF_BYTES + vaddr[db] + (32 * u + 16 * cp) * 128;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
+        const s16x4 hi =
+            __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p + 8 * 128));
+        const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
+        const u32x4 av = {lo2[0], lo2[1], hi2[0], hi2[1]};
+        va[db][cp] = __builtin_bit_cast(bf16x8, av);
+      }
   };
 
-  // One key tile, software pipelined against its neighbours.  On entry the tile's data is in
-  // buffer BUF, visible to every wave, and ka holds the K operands of its first sub-tile.  Per
-  // 32-key sub-tile: scores (8 MFMAs) -> weights (VALU) -> O update (8 MFMAs).  Before the last O
-  // update the workgroup synchronises: from then on nobody reads buffer BUF any more, so the loads
-  // of tile it+2 are started into it, and tile it+1 (in the other buffer) is known to have landed,
-  // so its first K operands are fetched while the last 8 MFMAs run.
-  //
-  // SAFE = false (fast pass): weights are exp2 of the raw scaled logits, i.e. the softmax reference
-  // is 0 for every row.  Any reference gives the same O / l; the choice only matters for range, and
-  // the caller checks the range afterwards.  No maximum is tracked and nothing is subtracted.
-  // SAFE = true: classic online softmax.  The accumulator of the score MFMA starts at -m_ref so the
-  // MFMA result is already relative to the reference, and m_ref is raised only when a tile exceeds
-  // it by more than 2^kRaise.
-  auto step = [&](auto bufc, auto safec, int it, bool ragged, int J_next2) {
-    constexpr int buf = decltype(bufc)::value;
+  const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
+  // weights of key pair j (registers 2j, 2j+1) of a score block: exp2, round to bf16, add to the
+  // row sum, store as word j of the two B operands
+  auto weigh_pair = [&](const f32x16& sc, u32x4 (&w)[2], int j) {
+    const unsigned pk = pack_bf16(__builtin_amdgcn_exp2f(sc[2 * j]), __builtin_amdgcn_exp2f(sc[2 * j + 1]));
+    l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, l_run, false);
+    w[j >> 2][j & 3] = pk;
+  };
+
+  // ---------------------------------------------------------------------------------------------
+  // Plain tile loop: per 32-key sub-tile scores (4 MFMAs) -> weights -> O update (4 MFMAs), one
+  // barrier per tile, the next tile's loads in flight meanwhile.  Used for the SAFE pass and for
+  // block 64.
+  //   SAFE = true: online softmax.  The accumulator of the score MFMA starts at -m_ref, so the MFMA
+  //   result is already relative to the reference, and m_ref is raised only when a sub-tile exceeds
+  //   it by more than 2^kRaise.  Keys of the ragged last tile that lie past the end are masked.
+  //   SAFE = false: reference 0, no maximum, no masking: the zero-filled keys past the end each add
+  //   exactly 2^0 = 1 to the row sum and nothing to O; pass() subtracts their count.
+  auto plain_loop = [&](auto safec, int& pad_keys) {
     constexpr bool SAFE = decltype(safec)::value;
-    const unsigned char* tile = smem + buf * BUF_BYTES;
-
+    if (count <= 0) return;
+    int J_cur = block_at(0);
+    issue(J_cur, 0);
+    for (int it = 0; it < count; ++it) {
+      const int buf = it & 1;
+      const int J_next = (it + 1 < count) ? block_at(it + 1) : 0;
+      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile `it` has landed
+      __syncthreads();                     // ... and so has everyone else's; buffer buf^1 is free
+      if (it + 1 < count) issue(J_next, buf ^ 1);
+      const bool ragged = (J_cur == nb - 1 && tail < B);
+      if (ragged && !SAFE) pad_keys += B - tail;
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-      const bool last = (mb == MB - 1);
-      // V^T operands of this sub-tile: [dim block][16-key chunk] = two 4-key transpose reads each
-      bf16x8 va[2][2];
+      for (int u = 0; u < NU; ++u) {
+        bf16x8 ka[4], va[2][2];
+        read_k(ka, buf, u);
+        read_v(va, buf, u);
+        const float base = (SAFE && m_ref != -INFINITY) ? m_ref : 0.f;
+        f32x16 sc;
 #pragma unroll
-      for (int db = 0; db < 2; ++db)
+        for (int i = 0; i < 16; ++i) sc[i] = -base;
 #pragma unroll
-        for (int cp = 0; cp < 2; ++cp) {
-          const int key0 = (2 * mb + cp) * 16;
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (s16x4 __attribute__((address_space(3)))*)(tile + vaddr[db] + key0 * 128));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (s16x4 __attribute__((address_space(3)))*)(tile + vaddr[db] + (key0 + 8) * 128));
-          const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
-          const u32x4 av = {lo2[0], lo2[1], hi2[0], hi2[1]};
-          va[db][cp] = __builtin_bit_cast(bf16x8, av);
-        }
-
-      // ---- S^T = K Q^T (- m_ref) for 32 keys x 64 queries ------------------------------------------
-      float base[2] = {0.f, 0.f};
-      f32x16 sc[2];
+        for (int c = 0; c < 4; ++c) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c], qf[c], sc, 0, 0, 0);
+        if constexpr (SAFE) {
+          if (ragged) {
 #pragma unroll
-      for (int b2 = 0; b2 < 2; ++b2) {
-        if constexpr (SAFE) base[b2] = (m_ref[b2] == -INFINITY) ? 0.f : m_ref[b2];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sc[b2][i] = SAFE ? -base[b2] : 0.f;
-      }
-#pragma unroll
-      for (int c = 0; c < 4; ++c)
-#pragma unroll
-        for (int b2 = 0; b2 < 2; ++b2)
-          sc[b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c], qf[b2][c], sc[b2], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      if (!last) read_k(buf, mb + 1);  // lands while the weights below are computed
-      if constexpr (SAFE) {
-        // Ragged last key block: its rows past the end were loaded as zeros (score 0, value 0).
-        // The running-max form masks them out; the fast pass instead lets each contribute a weight
-        // of exactly 2^0 = 1 to the row sum and nothing to O, and subtracts their count at the end.
-        if (ragged) {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int key = kh * KW + mb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-            if (key >= tail) {
-              sc[0][i] = -INFINITY;
-              sc[1][i] = -INFINITY;
+            for (int i = 0; i < 16; ++i) {
+              const int key = u * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
+              if (key >= tail) sc[i] = -INFINITY;
             }
           }
-        }
-      }
-
-      // ---- softmax weights, per query column -----------------------------------------------------
-      bf16x8 pf[2][2];
-#pragma unroll
-      for (int b2 = 0; b2 < 2; ++b2) {
-        if constexpr (SAFE) {
           float tmax = -INFINITY;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sc[b2][i]);
+          for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sc[i]);
           tmax = fmaxf(tmax, xor32(tmax));
-          const bool unset = m_ref[b2] == -INFINITY;
+          const bool unset = m_ref == -INFINITY;
           const bool raise = unset ? (tmax > -INFINITY) : (tmax > kRaise);
           if (__any(raise)) {  // rare after the first tile
             const float shift = raise ? tmax : 0.f;
             const float alpha = unset ? 1.f : exp2f(-shift);  // nothing accumulated yet while unset
-            if (raise) m_ref[b2] = base[b2] + shift;
-            l_run[b2] *= alpha;
+            if (raise) m_ref = base + shift;
+            l_run *= alpha;
 #pragma unroll
             for (int db = 0; db < 2; ++db)
 #pragma unroll
-              for (int i = 0; i < 16; ++i) o[db][b2][i] *= alpha;
+              for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) sc[b2][i] -= shift;
+            for (int i = 0; i < 16; ++i) sc[i] -= shift;
           }
         }
-        const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
-        float rowsum = l_run[b2];
+        u32x4 w[2];
 #pragma unroll
-        for (int cp = 0; cp < 2; ++cp) {
-          u32x4 w;
-#pragma unroll
-          for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-            for (int r2 = 0; r2 < 2; ++r2) {
-              const int i0 = 4 * (2 * cp + t2) + 2 * r2;
-              const unsigned pk = pack_bf16(__builtin_amdgcn_exp2f(sc[b2][i0]), __builtin_amdgcn_exp2f(sc[b2][i0 + 1]));
-              rowsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, rowsum, false);
-              w[2 * t2 + r2] = pk;
-            }
-          pf[b2][cp] = __builtin_bit_cast(bf16x8, w);
-        }
-        l_run[b2] = rowsum;
-      }
-      __builtin_amdgcn_sched_barrier(0);
-
-      if (last) {
-        // every LDS read of this tile has been issued; once all waves are here the buffer is free
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile it+1 has landed
-        __syncthreads();
-        if (it + 1 < count) read_k(buf ^ 1, 0);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-
-      // ---- O^T += V^T P^T, with the loads of tile it+2 slotted between the last MFMAs -------------
-#pragma unroll
-      for (int db = 0; db < 2; ++db)
-#pragma unroll
-        for (int cp = 0; cp < 2; ++cp)
-#pragma unroll
-          for (int b2 = 0; b2 < 2; ++b2) {
-            o[db][b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db][cp], pf[b2][cp], o[db][b2], 0, 0, 0);
-            if (last) {
-              if (it + 2 < count) issue_part(J_next2, buf, (db * 2 + cp) * 2 + b2);
-              __builtin_amdgcn_sched_barrier(0);
-            }
-          }
-    }
-  };
-
-  // A whole pass over the row's key tiles, then the merge of the two key halves: wave (qi, 1)
-  // parks its state in LDS as [qi][68 values][64 lanes] and wave (qi, 0) folds it in.  Returns
-  // true (to every thread of the workgroup) if the pass must be repeated in SAFE mode because a
-  // row sum or an output left the range in which the reference-free weights are trustworthy:
-  // a weight 2^s overflows for s >= 128 (the sum then exceeds the upper limit or O is not finite),
-  // and weights below 2^-126 flush to zero, which is harmless as long as the row sum is at least
-  // 2^-80 (at most 2^24 keys x 2^-126 lost, a relative error under 2^-22 ... 2^-29).
-  auto pass = [&](auto safec) -> bool {
-    constexpr bool SAFE = decltype(safec)::value;
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-      for (int b2 = 0; b2 < 2; ++b2)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[a][b2][i] = 0.f;
-    m_ref[0] = m_ref[1] = -INFINITY;
-    l_run[0] = l_run[1] = 0.f;
-    idx_cur = load_idx(0);
-    idx_next = load_idx(64);
-    // prologue: tile 0 -> buffer 0, wait for it, tile 1 -> buffer 1, first K operands
-    int J_cur = 0, J_nxt = 0;
-    if (count > 0) {
-      J_cur = block_at(0);
-      issue(J_cur, 0);
-      if (count > 1) J_nxt = block_at(1);
-      __builtin_amdgcn_s_waitcnt(0x0F70);
-      __syncthreads();
-      if (count > 1) issue(J_nxt, 1);
-      read_k(0, 0);
-    }
-    int pad_keys = 0;  // zero-filled keys past the end that the fast pass has summed as weight 1
-    auto tile_step = [&](auto bufc, int it, int J, int J_next2) {
-      const bool ragged = (J == nb - 1 && tail < B);
-      if (ragged) pad_keys += B - tail;
-      step(bufc, safec, it, ragged, J_next2);
-    };
-    for (int it = 0; it < count; it += 2) {
-      int J2 = (it + 2 < count) ? block_at(it + 2) : 0;
-      tile_step(std::integral_constant<int, 0>{}, it, J_cur, J2);
-      if (it + 1 >= count) break;
-      const int J3 = (it + 3 < count) ? block_at(it + 3) : 0;
-      tile_step(std::integral_constant<int, 1>{}, it + 1, J_nxt, J3);
-      J_cur = J2;
-      J_nxt = J3;
-    }
-    __syncthreads();  // every wave is done reading the tiles: LDS can be reused
-
-    float* park = reinterpret_cast<float*>(smem) + qi * 68 * 64;
-    if (kh == 1) {
-#pragma unroll
-      for (int db = 0; db < 2; ++db)
-#pragma unroll
-        for (int b2 = 0; b2 < 2; ++b2)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) park[((db * 2 + b2) * 16 + i) * 64 + lane] = o[db][b2][i];
-#pragma unroll
-      for (int b2 = 0; b2 < 2; ++b2) {
-        park[(64 + b2) * 64 + lane] = m_ref[b2];
-        park[(66 + b2) * 64 + lane] = l_run[b2];
-      }
-    }
-    __syncthreads();
-    bool bad = false;
-    float lt[2], mt[2];
-    if (kh == 0) {
-#pragma unroll
-      for (int b2 = 0; b2 < 2; ++b2) {
-        const float l1 = park[(66 + b2) * 64 + lane];
-        float a0 = 1.f, a1 = 1.f;
-        mt[b2] = 0.f;
-        if constexpr (SAFE) {
-          const float m1 = park[(64 + b2) * 64 + lane];
-          const float m0 = m_ref[b2];
-          mt[b2] = fmaxf(m0, m1);
-          const float mu = (mt[b2] == -INFINITY) ? 0.f : mt[b2];
-          a0 = exp2f(m0 - mu);  // exp2f(-inf) = 0 for a half that saw nothing
-          a1 = exp2f(m1 - mu);
-        }
-        float l = l_run[b2] * a0 + l1 * a1;
-        l += xor32(l);
-        if constexpr (!SAFE) l -= static_cast<float>(pad_keys);
-        lt[b2] = l;
-        if constexpr (!SAFE) bad = bad || !(l >= 0x1p-80f && l <= 0x1p100f);
+        for (int j = 0; j < 8; ++j) weigh_pair(sc, w, j);
 #pragma unroll
         for (int db = 0; db < 2; ++db)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            o[db][b2][i] = o[db][b2][i] * a0 + park[((db * 2 + b2) * 16 + i) * 64 + lane] * a1;
-            if constexpr (!SAFE) bad = bad || !(fabsf(o[db][b2][i]) < INFINITY);
-          }
+          for (int cp = 0; cp < 2; ++cp)
+            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db][cp], __builtin_bit_cast(bf16x8, w[cp]), o[db], 0,
+                                                            0, 0);
       }
+      J_cur = J_next;
     }
+  };
+
+  // ---------------------------------------------------------------------------------------------
+  // Fast pass for block 128: the same arithmetic as plain_loop<SAFE = false>, software pipelined
+  // inside the wave.  Unit n of a tile is its 32-key sub-tile n (0..3): scores QK(n) (4 MFMAs into
+  // 16 registers), weights W(n) (16 exp2, 8 packs, 8 dot2), O update PV(n) (4 MFMAs).  While the
+  // VALU works on W(n) the matrix pipe gets QK(n+1) and PV(n-1), one MFMA per four VALU
+  // instructions, so the wave's VALU and MFMA streams overlap instead of waiting for each other.
+  // LDS operands are fetched ahead of use: K of unit n+2 right after the last MFMA of QK(n+1), V of
+  // all four units during units 0 and 1.  In the middle of unit 2 every read of the tile has
+  // therefore been issued; there the workgroup synchronises once per tile: the next tile is known
+  // to have landed (its first K operands are read right away) and the current buffer is free, so
+  // the eight loads of the tile after next are issued into it, one after each following MFMA.
+  auto fast_loop = [&](int& pad_keys) {
+    if (count <= 0) return;
+    f32x16 sc[2];        // scores: [unit parity]
+    u32x4 pw[2][2];      // weights as packed bf16 pairs: [unit parity][16-key chunk]
+    bf16x8 ka[4];        // K operands of the unit whose scores are computed next
+    bf16x8 va[4][2][2];  // V^T operands: [unit][dim block][16-key chunk]
+#pragma unroll
+    for (int cp = 0; cp < 2; ++cp) {
+      pw[1][cp] = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int db = 0; db < 2; ++db) va[3][db][cp] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
+    }
+
+    // one unit: U = its number in the tile, P = U & 1 the parity of its score/weight registers.
+    // Slots 0..3: MFMA of QK(U+1) (if do_qk) + one weight pair; slots 4..7: MFMA of PV(U-1) + one
+    // weight pair.  mid(slot) places LDS reads, the barrier and loads after that slot's MFMA.
+    auto unit = [&](auto uc, auto doqkc, auto&& mid) {
+      constexpr int U = decltype(uc)::value, P = U & 1, Q = P ^ 1, UP = (U + 3) & 3;
+      constexpr bool do_qk = decltype(doqkc)::value;
+#define BSGA_SLOT(S_)                                                                                          \
+  {                                                                                                            \
+    if constexpr ((S_) < 4) {                                                                                  \
+      if constexpr (do_qk) {                                                                                   \
+        if constexpr ((S_) == 0) {                                                                             \
+          const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}; \
+          sc[Q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qf[0], zero, 0, 0, 0);                        \
+        } else {                                                                                               \
+          sc[Q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[(S_) & 3], qf[(S_) & 3], sc[Q], 0, 0, 0);          \
+        }                                                                                                      \
+      }                                                                                                        \
+    } else {                                                                                                   \
+      o[((S_) >> 1) & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[UP][((S_) >> 1) & 1][(S_) & 1],           \
+                                                                 __builtin_bit_cast(bf16x8, pw[Q][(S_) & 1]),  \
+                                                                 o[((S_) >> 1) & 1], 0, 0, 0);                 \
+    }                                                                                                          \
+    weigh_pair(sc[P], pw[P], (S_));                                                                            \
+    mid(Int<(S_)>{});                                                                                          \
+    __builtin_amdgcn_sched_barrier(0);                                                                         \
+  }
+      BSGA_SLOT(0) BSGA_SLOT(1) BSGA_SLOT(2) BSGA_SLOT(3) BSGA_SLOT(4) BSGA_SLOT(5) BSGA_SLOT(6) BSGA_SLOT(7)
+#undef BSGA_SLOT
+    };
+
+    // a whole tile.  On entry: sc[0] = QK(0) of this tile, ka = K operands of unit 1, pw[1] / va[3]
+    // = weights / V operands of the previous tile's unit 3 (zeros before the first tile).
+    auto tile = [&](auto bufc, auto hasnextc, int J, int J_next2) {
+      constexpr int buf = decltype(bufc)::value;
+      constexpr bool has_next = decltype(hasnextc)::value;
+      if (J == nb - 1 && tail < B) pad_keys += B - tail;
+      unit(Int<0>{}, std::true_type{}, [&](auto slot) {  // QK(1); PV(previous unit 3)
+        constexpr int S = decltype(slot)::value;
+        if constexpr (S == 3) read_k(ka, buf, 2);
+        if constexpr (S == 5) read_v(va[0], buf, 0);
+        if constexpr (S == 7) read_v(va[1], buf, 1);
+      });
+      unit(Int<1>{}, std::true_type{}, [&](auto slot) {  // QK(2); PV(0)
+        constexpr int S = decltype(slot)::value;
+        if constexpr (S == 3) read_k(ka, buf, 3);
+        if constexpr (S == 5) read_v(va[2], buf, 2);
+        if constexpr (S == 7) read_v(va[3], buf, 3);
+      });
+      unit(Int<2>{}, std::true_type{}, [&](auto slot) {  // QK(3); synchronise; PV(1) + loads 0..3
+        constexpr int S = decltype(slot)::value;
+        if constexpr (S == 3) {
+          __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of the next tile has landed
+          __syncthreads();                     // every read of this tile is complete in every wave
+          if constexpr (has_next) read_k(ka, buf ^ 1, 0);
+        }
+        if constexpr (S >= 4) issue_part(J_next2, buf, S - 4);
+      });
+      unit(Int<3>{}, hasnextc, [&](auto slot) {  // QK(next tile's unit 0); PV(2) + loads 4..7
+        constexpr int S = decltype(slot)::value;
+        if constexpr (S == 3 && has_next) read_k(ka, buf ^ 1, 1);
+        if constexpr (S >= 4) issue_part(J_next2, buf, S);
+      });
+    };
+
+    // ---- prologue: tile 0 -> buffer 0, tile 1 -> buffer 1, QK(0), K operands of unit 1 ------------
+    int J_cur = block_at(0);
+    issue(J_cur, 0);
+    int J_nxt = (count > 1) ? block_at(1) : J_cur;
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    if (count > 1) issue(J_nxt, 1);
+    read_k(ka, 0, 0);
+    {
+      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qf[0], zero, 0, 0, 0);
+#pragma unroll
+      for (int c = 1; c < 4; ++c) sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c], qf[c], sc[0], 0, 0, 0);
+    }
+    read_k(ka, 0, 1);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- all tiles but the last one or two, two per iteration so the buffer index is a constant ----
+    int T = 0;
+    for (; T + 2 < count; T += 2) {
+      const int J2 = block_at(T + 2);  // the tile after next
+      tile(Int<0>{}, std::true_type{}, J_cur, J2);
+      // at the end of the list: one more (harmless) load of a valid tile into the freed buffer
+      const int J3 = (T + 3 < count) ? block_at(T + 3) : J_nxt;
+      tile(Int<1>{}, std::true_type{}, J_nxt, J3);
+      J_cur = J2;
+      J_nxt = J3;
+    }
+    // ---- the last one or two tiles ----------------------------------------------------------------
+    if (T + 2 == count) {
+      tile(Int<0>{}, std::true_type{}, J_cur, J_cur);
+      tile(Int<1>{}, std::false_type{}, J_nxt, J_nxt);
+    } else {
+      tile(Int<0>{}, std::false_type{}, J_cur, J_cur);
+    }
+    // ---- epilogue: PV of the last unit ------------------------------------------------------------
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int cp = 0; cp < 2; ++cp)
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[3][db][cp], __builtin_bit_cast(bf16x8, pw[1][cp]), o[db], 0,
+                                                        0, 0);
+  };
+
+  // A whole pass over the row's key tiles, then the output.  Returns true (to every thread of the
+  // workgroup) if the fast pass must be repeated in SAFE mode because a row sum or an output left
+  // the range in which reference-free weights are trustworthy: a weight 2^s overflows for s >= 128
+  // (the row sum then exceeds the upper limit, or O is not finite), and weights below 2^-126 flush
+  // to zero, which is harmless as long as the row sum is at least 2^-80 (at most 2^24 keys x 2^-126
+  // lost: a relative error under 2^-22).
+  auto pass = [&](auto safec) -> bool {
+    constexpr bool SAFE = decltype(safec)::value;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+    m_ref = -INFINITY;
+    l_run = 0.f;
+    idx_cur = load_idx(0);
+    idx_next = load_idx(64);
+    int pad_keys = 0;  // zero-filled keys past the end that the fast pass has summed as weight 1
+    if constexpr (!SAFE && B == 128) fast_loop(pad_keys);
+    else plain_loop(safec, pad_keys);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // no direct-to-LDS load may still be in flight
+
+    float l = l_run + xor32(l_run);
     if constexpr (!SAFE) {
+      l -= static_cast<float>(pad_keys);
+      bool bad = !(l >= 0x1p-80f && l <= 0x1p100f);
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) bad = bad || !(fabsf(o[db][i]) < INFINITY);
+      if (count <= 0) bad = false;  // an empty row is zeros by definition, not a range problem
       if (__syncthreads_or(bad)) return true;
     }
-    if (kh == 0) {
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    if (qrow < n_tokens) {
 #pragma unroll
-      for (int b2 = 0; b2 < 2; ++b2) {
-        const float inv = lt[b2] > 0.f ? 1.f / lt[b2] : 0.f;
-        const int64_t row = int64_t(I) * B + qi * 64 + b2 * 32 + n;
-        if (row < n_tokens) {
+      for (int db = 0; db < 2; ++db)
 #pragma unroll
-          for (int db = 0; db < 2; ++db)
-#pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-              const f32x16& x = o[db][b2];
-              const int i = 4 * r4;
-              const u32x2 w = {pack_bf16(x[i] * inv, x[i + 1] * inv), pack_bf16(x[i + 2] * inv, x[i + 3] * inv)};
-              *reinterpret_cast<u32x2*>(out + (int64_t(h) * n_tokens + row) * kD + db * 32 + 8 * r4 + 4 * g) = w;
-            }
-          if (lse != nullptr && g == 0)
-            lse[int64_t(h) * n_tokens + row] = lt[b2] > 0.f ? (mt[b2] + log2f(lt[b2])) * kLn2 : -INFINITY;
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const f32x16& x = o[db];
+          const int i = 4 * r4;
+          const u32x2 w = {pack_bf16(x[i] * inv, x[i + 1] * inv), pack_bf16(x[i + 2] * inv, x[i + 3] * inv)};
+          *reinterpret_cast<u32x2*>(out + (int64_t(h) * n_tokens + qrow) * kD + db * 32 + 8 * r4 + 4 * g) = w;
         }
+      if (lse != nullptr && g == 0) {
+        const float mref = (SAFE && m_ref != -INFINITY) ? m_ref : 0.f;
+        lse[int64_t(h) * n_tokens + qrow] = l > 0.f ? (mref + log2f(l)) * kLn2 : -INFINITY;
       }
     }
     return false;
   };
 
   if (pass(std::false_type{})) {
-    __syncthreads();  // the parked state has been read by everyone: LDS is free for tiles again
     pass(std::true_type{});
   }
 }
