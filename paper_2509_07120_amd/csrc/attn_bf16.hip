@@ -8,7 +8,9 @@
 // share a CU (two waves per SIMD).
 //
 // Data movement.  K and V tiles go HBM/L2 -> LDS with direct-to-LDS loads (16 bytes per lane, no
-// staging registers), double buffered.  Tiles stay row-major [key][64]; only the order of the eight
+// staging registers) into two K buffers and three V buffers (K of a tile is consumed early in the
+// tile, V late, so V needs the extra stage for both to be loaded a full tile ahead with a single
+// workgroup barrier per tile).  Tiles stay row-major [key][64]; only the order of the eight
 // 16-byte chunks inside a row is permuted (XOR swizzle, chosen per tensor) so the operand reads
 // below are bank-conflict free.  gfx950's LDS delivers ~250 B/clk per CU for 16-byte reads, which
 // is what lets every wave read the whole tile.
@@ -103,8 +105,8 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   constexpr int NW = B / 32;              // waves per workgroup (2 B threads), 32 query rows each
   constexpr int NU = B / 32;              // 32-key sub-tiles ("units") per key tile
   constexpr int TILE_BYTES = B * 128;     // one K or V tile
-  constexpr int BUF_BYTES = 2 * TILE_BYTES;
-  extern __shared__ __align__(1024) unsigned char smem[];  // [2 buffers][K tile | V tile]
+  constexpr int V_BASE = 2 * TILE_BYTES;  // LDS layout: K buffers 0, 1, then V buffers 0, 1, 2
+  extern __shared__ __align__(16) unsigned char smem[];
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -171,7 +173,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
 #pragma unroll
     for (int db = 0; db < 2; ++db) {
       const int cc = db * 4 + 2 * (G & 1) + (j >> 1);
-      vaddr[db] = TILE_BYTES + keyl * 128 + ((cc ^ swz_v(keyl)) << 4) + (j & 1) * 8;
+      vaddr[db] = V_BASE + keyl * 128 + ((cc ^ swz_v(keyl)) << 4) + (j & 1) * 8;
     }
   }
 
@@ -200,38 +202,38 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     const int J = __builtin_amdgcn_readlane(idx_cur, it & 63);
     return min(max(J, 0), nb - 1);
   };
-  // Direct-to-LDS load number i2 (0..7) of key tile J into buffer `buf`: even i2 moves 1 KB of the
-  // K tile, odd i2 1 KB of the V tile.  Rows of a ragged last tile that lie past the end of the
-  // head's buffer fail the hardware bounds check, which makes the load write zeros for them.
-  auto issue_part = [&](int J, int buf, int i2) {
+  // Direct-to-LDS load number i2 (0..7) of key tile J: even i2 moves 1 KB of the K tile into K
+  // buffer kb, odd i2 1 KB of the V tile into V buffer vb.  Rows of a ragged last tile that lie past
+  // the end of the head's buffer fail the hardware bounds check, which makes the load write zeros.
+  auto issue_part = [&](int J, int kb, int vb, int i2) {
     const int i = i2 >> 1;
     const bool is_v = (i2 & 1) != 0;
     const unsigned soff = static_cast<unsigned>(J) * TILE_BYTES;
-    const unsigned dst = smem_addr + buf * BUF_BYTES + wave * 1024 + (is_v ? TILE_BYTES : 0) + NW * i * 1024;
+    const unsigned dst = smem_addr + wave * 1024 + NW * i * 1024 + (is_v ? V_BASE + vb * TILE_BYTES : kb * TILE_BYTES);
     if (is_v) {
       dma16(vrsrc, voff, soff + i * NW * 1024, dst);
     } else {
       dma16(krsrc, koff[i % KN], soff + (i / KN) * KN * NW * 1024, dst);
     }
   };
-  auto issue = [&](int J, int buf) {
+  auto issue = [&](int J, int kb, int vb) {
 #pragma unroll
-    for (int i2 = 0; i2 < 8; ++i2) issue_part(J, buf, i2);
+    for (int i2 = 0; i2 < 8; ++i2) issue_part(J, kb, vb, i2);
   };
 
-  // K operands (A of S^T = K Q^T) of 32-key sub-tile u of the tile in buffer `buf`
-  auto read_k = [&](bf16x8 (&ka)[4], int buf, int u) {
+  // K operands (A of S^T = K Q^T) of 32-key sub-tile u; kbase[c] = kaddr[c] + byte offset of the K buffer
+  auto read_k = [&](bf16x8 (&ka)[4], const unsigned (&kbase)[4], int u) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c)
-      ka[c] = *LDS_PTR(bf16x8, smem + buf * BUF_BYTES + kaddr[(u & 1) ? (c ^ 2) : c] + u * 4096);
+    for (int c = 0; c < 4; ++c) ka[c] = *LDS_PTR(bf16x8, smem + kbase[(u & 1) ? (c ^ 2) : c] + u * 4096);
   };
-  // V^T operands (A of O^T += V^T P^T) of sub-tile u: [dim block][16-key chunk]
-  auto read_v = [&](bf16x8 (&va)[2][2], int buf, int u) {
+  // V^T operands (A of O^T += V^T P^T) of sub-tile u: [dim block][16-key chunk];
+  // vbase[db] = vaddr[db] + byte offset of the V buffer
+  auto read_v = [&](bf16x8 (&va)[2][2], const unsigned (&vbase)[2], int u) {
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
       for (int cp = 0; cp < 2; ++cp) {
-        const unsigned char* p = smem + buf * BUF_BYTES + vaddr[db] + (32 * u + 16 * cp) * 128;
+        const unsigned char* p = smem + vbase[db] + (32 * u + 16 * cp) * 128;
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
         const s16x4 hi =
             __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p + 8 * 128));
@@ -239,6 +241,14 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
         const u32x4 av = {lo2[0], lo2[1], hi2[0], hi2[1]};
         va[db][cp] = __builtin_bit_cast(bf16x8, av);
       }
+  };
+  auto k_bases = [&](unsigned (&kbase)[4], int kb) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) kbase[c] = kaddr[c] + kb * TILE_BYTES;
+  };
+  auto v_bases = [&](unsigned (&vbase)[2], int vb) {
+#pragma unroll
+    for (int db = 0; db < 2; ++db) vbase[db] = vaddr[db] + vb * TILE_BYTES;
   };
 
   const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
@@ -263,20 +273,23 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     constexpr bool SAFE = decltype(safec)::value;
     if (count <= 0) return;
     int J_cur = block_at(0);
-    issue(J_cur, 0);
+    issue(J_cur, 0, 0);
     for (int it = 0; it < count; ++it) {
-      const int buf = it & 1;
+      const int buf = it & 1;  // this loop uses K buffer and V buffer number it % 2
       const int J_next = (it + 1 < count) ? block_at(it + 1) : 0;
       __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile `it` has landed
-      __syncthreads();                     // ... and so has everyone else's; buffer buf^1 is free
-      if (it + 1 < count) issue(J_next, buf ^ 1);
+      __syncthreads();                     // ... and so has everyone else's; buffers buf^1 are free
+      if (it + 1 < count) issue(J_next, buf ^ 1, buf ^ 1);
+      unsigned kbase[4], vbase[2];
+      k_bases(kbase, buf);
+      v_bases(vbase, buf);
       const bool ragged = (J_cur == nb - 1 && tail < B);
       if (ragged && !SAFE) pad_keys += B - tail;
 #pragma unroll
       for (int u = 0; u < NU; ++u) {
         bf16x8 ka[4], va[2][2];
-        read_k(ka, buf, u);
-        read_v(va, buf, u);
+        read_k(ka, kbase, u);
+        read_v(va, vbase, u);
         const float base = (SAFE && m_ref != -INFINITY) ? m_ref : 0.f;
         f32x16 sc;
 #pragma unroll
@@ -330,29 +343,31 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   // 16 registers), weights W(n) (16 exp2, 8 packs, 8 dot2), O update PV(n) (4 MFMAs).  While the
   // VALU works on W(n) the matrix pipe gets QK(n+1) and PV(n-1), one MFMA per four VALU
   // instructions, so the wave's VALU and MFMA streams overlap instead of waiting for each other.
-  // LDS operands are fetched ahead of use: K of unit n+2 right after the last MFMA of QK(n+1), V of
-  // all four units during units 0 and 1.  In the middle of unit 2 every read of the tile has
-  // therefore been issued; there the workgroup synchronises once per tile: the next tile is known
-  // to have landed (its first K operands are read right away) and the current buffer is free, so
-  // the eight loads of the tile after next are issued into it, one after each following MFMA.
+  // LDS operands are fetched a whole unit ahead of their use, into alternating register sets: K of
+  // unit n+2 and V of unit n at the start of unit n.  Tile T lives in K buffer T%2 and V buffer T%3.
+  // The workgroup synchronises once per tile, at the start of unit 2: by then every K read of the
+  // tile has been issued and tile T+1 has landed, so the first K operands of tile T+1 are read right
+  // away and the loads of tile T+2 are started (K into the buffer just vacated, V into the buffer of
+  // tile T-1), one after each of the following MFMAs: a full tile ahead of their use.
   auto fast_loop = [&](int& pad_keys) {
     if (count <= 0) return;
     f32x16 sc[2];        // scores: [unit parity]
     u32x4 pw[2][2];      // weights as packed bf16 pairs: [unit parity][16-key chunk]
-    bf16x8 ka[4];        // K operands of the unit whose scores are computed next
-    bf16x8 va[4][2][2];  // V^T operands: [unit][dim block][16-key chunk]
+    bf16x8 ka[2][4];     // K operands: [unit parity][16-dim chunk]
+    bf16x8 va[2][2][2];  // V^T operands: [unit parity][dim block][16-key chunk]
+    unsigned kbase[4], knext[4], vbase[2];  // LDS addresses of this tile's K, the next tile's K, this tile's V
 #pragma unroll
     for (int cp = 0; cp < 2; ++cp) {
       pw[1][cp] = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
-      for (int db = 0; db < 2; ++db) va[3][db][cp] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
+      for (int db = 0; db < 2; ++db) va[1][db][cp] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
     }
 
-    // one unit: U = its number in the tile, P = U & 1 the parity of its score/weight registers.
+    // one unit: U = its number in the tile, P = U & 1 the parity of its registers, Q the other one.
     // Slots 0..3: MFMA of QK(U+1) (if do_qk) + one weight pair; slots 4..7: MFMA of PV(U-1) + one
     // weight pair.  mid(slot) places LDS reads, the barrier and loads after that slot's MFMA.
     auto unit = [&](auto uc, auto doqkc, auto&& mid) {
-      constexpr int U = decltype(uc)::value, P = U & 1, Q = P ^ 1, UP = (U + 3) & 3;
+      constexpr int U = decltype(uc)::value, P = U & 1, Q = P ^ 1;
       constexpr bool do_qk = decltype(doqkc)::value;
 #define BSGA_SLOT(S_)                                                                                          \
   {                                                                                                            \
@@ -360,13 +375,13 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
       if constexpr (do_qk) {                                                                                   \
         if constexpr ((S_) == 0) {                                                                             \
           const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}; \
-          sc[Q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qf[0], zero, 0, 0, 0);                        \
+          sc[Q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[Q][0], qf[0], zero, 0, 0, 0);                     \
         } else {                                                                                               \
-          sc[Q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[(S_) & 3], qf[(S_) & 3], sc[Q], 0, 0, 0);          \
+          sc[Q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[Q][(S_) & 3], qf[(S_) & 3], sc[Q], 0, 0, 0);       \
         }                                                                                                      \
       }                                                                                                        \
     } else {                                                                                                   \
-      o[((S_) >> 1) & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[UP][((S_) >> 1) & 1][(S_) & 1],           \
+      o[((S_) >> 1) & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[Q][((S_) >> 1) & 1][(S_) & 1],            \
                                                                  __builtin_bit_cast(bf16x8, pw[Q][(S_) & 1]),  \
                                                                  o[((S_) >> 1) & 1], 0, 0, 0);                 \
     }                                                                                                          \
@@ -378,81 +393,82 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
 #undef BSGA_SLOT
     };
 
-    // a whole tile.  On entry: sc[0] = QK(0) of this tile, ka = K operands of unit 1, pw[1] / va[3]
-    // = weights / V operands of the previous tile's unit 3 (zeros before the first tile).
-    auto tile = [&](auto bufc, auto hasnextc, int J, int J_next2) {
-      constexpr int buf = decltype(bufc)::value;
+    // a whole tile T (K buffer kb = T%2, V buffer vb = T%3; the tile after next goes to kb and vb2).
+    // On entry: sc[0] = QK(0) of this tile, ka[1] = K operands of unit 1, pw[1] / va[1] = weights /
+    // V operands of the previous tile's unit 3 (zeros before the first tile).
+    auto tile = [&](auto hasnextc, int J, int J_next2, int kb, int vb, int vb2) {
       constexpr bool has_next = decltype(hasnextc)::value;
       if (J == nb - 1 && tail < B) pad_keys += B - tail;
+      k_bases(kbase, kb);
+      k_bases(knext, kb ^ 1);
+      v_bases(vbase, vb);
       unit(Int<0>{}, std::true_type{}, [&](auto slot) {  // QK(1); PV(previous unit 3)
         constexpr int S = decltype(slot)::value;
-        if constexpr (S == 3) read_k(ka, buf, 2);
-        if constexpr (S == 5) read_v(va[0], buf, 0);
-        if constexpr (S == 7) read_v(va[1], buf, 1);
+        if constexpr (S == 0) read_k(ka[0], kbase, 2);
+        if constexpr (S == 1) read_v(va[0], vbase, 0);
       });
       unit(Int<1>{}, std::true_type{}, [&](auto slot) {  // QK(2); PV(0)
         constexpr int S = decltype(slot)::value;
-        if constexpr (S == 3) read_k(ka, buf, 3);
-        if constexpr (S == 5) read_v(va[2], buf, 2);
-        if constexpr (S == 7) read_v(va[3], buf, 3);
+        if constexpr (S == 0) read_k(ka[1], kbase, 3);
+        if constexpr (S == 1) read_v(va[1], vbase, 1);
       });
       unit(Int<2>{}, std::true_type{}, [&](auto slot) {  // QK(3); synchronise; PV(1) + loads 0..3
         constexpr int S = decltype(slot)::value;
-        if constexpr (S == 3) {
+        if constexpr (S == 0) {
           __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of the next tile has landed
-          __syncthreads();                     // every read of this tile is complete in every wave
-          if constexpr (has_next) read_k(ka, buf ^ 1, 0);
+          __syncthreads();                     // every K read of this tile, every read of the previous one, is complete
+          if constexpr (has_next) read_k(ka[0], knext, 0);
         }
-        if constexpr (S >= 4) issue_part(J_next2, buf, S - 4);
+        if constexpr (S == 1) read_v(va[0], vbase, 2);
+        if constexpr (S >= 4) issue_part(J_next2, kb, vb2, S - 4);
       });
       unit(Int<3>{}, hasnextc, [&](auto slot) {  // QK(next tile's unit 0); PV(2) + loads 4..7
         constexpr int S = decltype(slot)::value;
-        if constexpr (S == 3 && has_next) read_k(ka, buf ^ 1, 1);
-        if constexpr (S >= 4) issue_part(J_next2, buf, S);
+        if constexpr (S == 0 && has_next) read_k(ka[1], knext, 1);
+        if constexpr (S == 1) read_v(va[1], vbase, 3);
+        if constexpr (S >= 4) issue_part(J_next2, kb, vb2, S);
       });
     };
 
-    // ---- prologue: tile 0 -> buffer 0, tile 1 -> buffer 1, QK(0), K operands of unit 1 ------------
+    // ---- prologue: tiles 0 and 1 on their way, QK(0), K operands of unit 1 -------------------------
     int J_cur = block_at(0);
-    issue(J_cur, 0);
-    int J_nxt = (count > 1) ? block_at(1) : J_cur;
+    issue(J_cur, 0, 0);
+    int J_nxt = J_cur;
+    if (count > 1) {
+      J_nxt = block_at(1);
+      issue(J_nxt, 1, 1);
+    }
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
-    if (count > 1) issue(J_nxt, 1);
-    read_k(ka, 0, 0);
+    k_bases(kbase, 0);
+    read_k(ka[0], kbase, 0);
     {
       const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qf[0], zero, 0, 0, 0);
+      sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0][0], qf[0], zero, 0, 0, 0);
 #pragma unroll
-      for (int c = 1; c < 4; ++c) sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c], qf[c], sc[0], 0, 0, 0);
+      for (int c = 1; c < 4; ++c) sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0][c], qf[c], sc[0], 0, 0, 0);
     }
-    read_k(ka, 0, 1);
+    read_k(ka[1], kbase, 1);
     __builtin_amdgcn_sched_barrier(0);
 
-    // ---- all tiles but the last one or two, two per iteration so the buffer index is a constant ----
-    int T = 0;
-    for (; T + 2 < count; T += 2) {
-      const int J2 = block_at(T + 2);  // the tile after next
-      tile(Int<0>{}, std::true_type{}, J_cur, J2);
-      // at the end of the list: one more (harmless) load of a valid tile into the freed buffer
-      const int J3 = (T + 3 < count) ? block_at(T + 3) : J_nxt;
-      tile(Int<1>{}, std::true_type{}, J_nxt, J3);
-      J_cur = J2;
-      J_nxt = J3;
+    // ---- all tiles but the last --------------------------------------------------------------------
+    int vb = 0;
+    for (int T = 0; T + 1 < count; ++T) {
+      // the tile after next; at the end of the list one more (harmless) load of a valid tile
+      const int J2 = (T + 2 < count) ? block_at(T + 2) : J_cur;
+      const int vb2 = (vb == 0) ? 2 : vb - 1;  // (T + 2) % 3 == (T - 1) % 3
+      tile(std::true_type{}, J_cur, J2, T & 1, vb, vb2);
+      J_cur = J_nxt;
+      J_nxt = J2;
+      vb = (vb == 2) ? 0 : vb + 1;
     }
-    // ---- the last one or two tiles ----------------------------------------------------------------
-    if (T + 2 == count) {
-      tile(Int<0>{}, std::true_type{}, J_cur, J_cur);
-      tile(Int<1>{}, std::false_type{}, J_nxt, J_nxt);
-    } else {
-      tile(Int<0>{}, std::false_type{}, J_cur, J_cur);
-    }
-    // ---- epilogue: PV of the last unit ------------------------------------------------------------
+    // ---- the last tile, then the O update of its last unit -----------------------------------------
+    tile(std::false_type{}, J_cur, J_cur, (count - 1) & 1, vb, (vb == 0) ? 2 : vb - 1);
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
       for (int cp = 0; cp < 2; ++cp)
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[3][db][cp], __builtin_bit_cast(bf16x8, pw[1][cp]), o[db], 0,
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[1][db][cp], __builtin_bit_cast(bf16x8, pw[1][cp]), o[db], 0,
                                                         0, 0);
   };
 
@@ -486,7 +502,16 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
 #pragma unroll
         for (int i = 0; i < 16; ++i) bad = bad || !(fabsf(o[db][i]) < INFINITY);
       if (count <= 0) bad = false;  // an empty row is zeros by definition, not a range problem
-      if (__syncthreads_or(bad)) return true;
+      // workgroup-wide OR through one LDS word (the tile buffers are idle by now)
+      volatile int* flag = reinterpret_cast<volatile int*>(smem);
+      __syncthreads();
+      if (tid == 0) *flag = 0;
+      __syncthreads();
+      if (bad) *flag = 1;
+      __syncthreads();
+      const bool any_bad = *flag != 0;
+      __syncthreads();
+      if (any_bad) return true;
     }
     const float inv = l > 0.f ? 1.f / l : 0.f;
     if (qrow < n_tokens) {
@@ -527,15 +552,24 @@ int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int
   unsigned short* op = static_cast<unsigned short*>(out);
   if (getenv("BSGA_DEBUG") != nullptr) {
     int n64 = -1, n128 = -1;
-    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n64, attn_bf16_kernel<64>, 128, 4 * 64 * 128);
-    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n128, attn_bf16_kernel<128>, 256, 4 * 128 * 128);
+    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n64, attn_bf16_kernel<64>, 128, 5 * 64 * 128);
+    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n128, attn_bf16_kernel<128>, 256, 5 * 128 * 128);
     fprintf(stderr, "[bsga] attention occupancy (workgroups per CU): block 64 -> %d, block 128 -> %d\n", n64, n128);
   }
+  // 5 tile buffers (2 K + 3 V): 80 KB for block 128, above the 64 KB a kernel gets without asking
+  static bool lds_limit_raised = false;
+  if (!lds_limit_raised) {
+    if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<128>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 5 * 128 * 128),
+                           "bsga bf16 attention: raising the dynamic LDS limit"))
+      return rc;
+    lds_limit_raised = true;
+  }
   if (block == 64) {
-    hipLaunchKernelGGL((attn_bf16_kernel<64>), grid, dim3(128), 4 * 64 * 128, stream, qp, kp, vp, op, lse, kv_idx,
+    hipLaunchKernelGGL((attn_bf16_kernel<64>), grid, dim3(128), 5 * 64 * 128, stream, qp, kp, vp, op, lse, kv_idx,
                        kv_cnt, idx_stride, n_tokens, nb, scale_log2);
   } else {
-    hipLaunchKernelGGL((attn_bf16_kernel<128>), grid, dim3(256), 4 * 128 * 128, stream, qp, kp, vp, op, lse, kv_idx,
+    hipLaunchKernelGGL((attn_bf16_kernel<128>), grid, dim3(256), 5 * 128 * 128, stream, qp, kp, vp, op, lse, kv_idx,
                        kv_cnt, idx_stride, n_tokens, nb, scale_log2);
   }
   return check_hip(hipGetLastError(), "bsga bf16 attention launch");
