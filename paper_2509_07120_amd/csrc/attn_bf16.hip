@@ -3,17 +3,16 @@
 // weights in the log2 domain.
 //
 // Work split.  One workgroup per (head, query block of B rows); it walks the row's kept key
-// blocks (tiles of B keys).  Each of the B/32 waves owns 32 query rows and sees every key of a
-// tile, so a wave's softmax state is private and nothing is merged at the end.  Two workgroups
-// share a CU (two waves per SIMD).
+// blocks (tiles of B keys).  Waves are arranged WQ x 2: wave (qi, kh) owns 64 query rows (qi)
+// and one half of every key tile (kh), so each K/V operand fetched from LDS into registers feeds
+// two MFMAs (register-file traffic, not LDS bandwidth, is what this saves: LDS read data and MFMA
+// operands share the VGPR ports).  The two key halves keep independent softmax states that are
+// merged once at the end.  Two workgroups share a CU (two waves per SIMD).
 //
 // Data movement.  K and V tiles go HBM/L2 -> LDS with direct-to-LDS loads (16 bytes per lane, no
-// staging registers) into two K buffers and three V buffers (K of a tile is consumed early in the
-// tile, V late, so V needs the extra stage for both to be loaded a full tile ahead with a single
-// workgroup barrier per tile).  Tiles stay row-major [key][64]; only the order of the eight
-// 16-byte chunks inside a row is permuted (XOR swizzle, chosen per tensor) so the operand reads
-// below are bank-conflict free.  gfx950's LDS delivers ~250 B/clk per CU for 16-byte reads, which
-// is what lets every wave read the whole tile.
+// staging registers), double buffered, with one workgroup barrier per tile.  Tiles stay row-major
+// [key][64]; only the order of the eight 16-byte chunks inside a row is permuted (XOR swizzle,
+// chosen per tensor) so the operand reads below are bank-conflict free.
 //
 // Register layouts.  Scores are produced transposed, S^T = K Q^T (M = keys, N = queries): in the
 // 32x32 accumulator layout lane (n = lane%32, g = lane/32) holds, for query n, the keys
@@ -102,10 +101,12 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     const unsigned char* __restrict__ q, const unsigned char* __restrict__ k, const unsigned char* __restrict__ v,
     unsigned short* __restrict__ out, float* __restrict__ lse, const int32_t* __restrict__ kv_idx,
     const int32_t* __restrict__ kv_cnt, int idx_stride, int64_t n_tokens, int nb, float scale_log2) {
-  constexpr int NW = B / 32;              // waves per workgroup (2 B threads), 32 query rows each
-  constexpr int NU = B / 32;              // 32-key sub-tiles ("units") per key tile
+  constexpr int WQ = B / 64;              // waves along queries (64 rows each)
+  constexpr int KW = B / 2;               // keys per wave per tile
+  constexpr int NH = KW / 32;             // 32-key sub-tiles per wave per tile
+  constexpr int NW = B / 32;              // waves per workgroup
   constexpr int TILE_BYTES = B * 128;     // one K or V tile
-  constexpr int V_BASE = 2 * TILE_BYTES;  // LDS layout: K buffers 0, 1, then V buffers 0, 1, 2
+  constexpr int V_BASE = 2 * TILE_BYTES;  // LDS layout: K buffers 0, 1, then V buffers 0, 1
   extern __shared__ __align__(16) unsigned char smem[];
 
   const int tid = threadIdx.x;
@@ -113,6 +114,8 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   const int lane = tid & 63;
   const int n = lane & 31;
   const int g = lane >> 5;
+  const int qi = wave % WQ;
+  const int kh = wave / WQ;
   const int I = blockIdx.x;
   const int h = blockIdx.y;
   const int64_t head_bytes = int64_t(h) * n_tokens * 128;
@@ -124,21 +127,25 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   const unsigned smem_addr =
       static_cast<unsigned>(reinterpret_cast<size_t>((__attribute__((address_space(3))) unsigned char*)smem));
 
-  // ---- Q fragments (B operand of S^T = K Q^T), pre-scaled: lane (n, g) holds dims 16c + 8g .. +7
-  const int64_t qrow = int64_t(I) * B + wave * 32 + n;
-  bf16x8 qf[4];
+  // ---- Q fragments (B operand of S^T = K Q^T), pre-scaled: [query half][16-dim chunk]; lane (n, g)
+  // holds dims 16c + 8g .. +7 of query row 32 b + n of the wave's 64
+  bf16x8 qf[2][4];
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    u32x4 x = {0u, 0u, 0u, 0u};
-    if (qrow < n_tokens) x = *reinterpret_cast<const u32x4*>(q + head_bytes + qrow * 128 + (2 * c + g) * 16);
-    u32x4 y;
+  for (int b2 = 0; b2 < 2; ++b2) {
+    const int64_t row = int64_t(I) * B + qi * 64 + b2 * 32 + n;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const float lo = __uint_as_float(x[e] << 16) * scale_log2;
-      const float hi = __uint_as_float(x[e] & 0xffff0000u) * scale_log2;
-      y[e] = pack_bf16(lo, hi);
+    for (int c = 0; c < 4; ++c) {
+      u32x4 x = {0u, 0u, 0u, 0u};
+      if (row < n_tokens) x = *reinterpret_cast<const u32x4*>(q + head_bytes + row * 128 + (2 * c + g) * 16);
+      u32x4 y;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float lo = __uint_as_float(x[e] << 16) * scale_log2;
+        const float hi = __uint_as_float(x[e] & 0xffff0000u) * scale_log2;
+        y[e] = pack_bf16(lo, hi);
+      }
+      qf[b2][c] = __builtin_bit_cast(bf16x8, y);
     }
-    qf[c] = __builtin_bit_cast(bf16x8, y);
   }
 
   // ---- per-lane constants -------------------------------------------------------------------------
@@ -158,18 +165,21 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     koff[i] = r * 128 + ((dma_pc ^ swz_k(r)) << 4);
   }
   const unsigned voff = dma_r0 * 128 + ((dma_pc ^ swz_v(dma_r0)) << 4);
-  // K operand reads (ds_read_b128) of sub-tile u: row r = 32u + n, logical chunk 2c + g.  Since
-  // swz_k(r + 32) = swz_k(r) ^ 4, an odd sub-tile reads chunk c where an even one reads chunk c ^ 2.
+  // K operand reads (ds_read_b128) of the wave's sub-tile u: row r = kh*KW + 32u + n, logical chunk
+  // 2c + g.  Since swz_k(r + 32) = swz_k(r) ^ 4, sub-tile 1 reads chunk c where sub-tile 0 reads c ^ 2.
   unsigned kaddr[4];
+  {
+    const int r = kh * KW + n;
 #pragma unroll
-  for (int c = 0; c < 4; ++c) kaddr[c] = n * 128 + (((2 * c + g) ^ swz_k(n)) << 4);
+    for (int c = 0; c < 4; ++c) kaddr[c] = r * 128 + (((2 * c + g) ^ swz_k(r)) << 4);
+  }
   // V operand reads (transpose read, 8 bytes per lane): 16-lane group G = lane/16 covers dims
   // db*32 + 16*(G&1) .. +15 for key-slot half g = G/2; inside the group lane i names key
-  // m = i/4 of the four and the dim quad j = i%4.  Key = 32u + 16cp + 8t + 4g + m.
+  // m = i/4 of the four and the dim quad j = i%4.  Key = kh*KW + 32u + 16cp + 8t + 4g + m.
   unsigned vaddr[2];
   {
     const int i16 = lane & 15, m = i16 >> 2, j = i16 & 3, G = lane >> 4;
-    const int keyl = 4 * g + m;
+    const int keyl = kh * KW + 4 * g + m;
 #pragma unroll
     for (int db = 0; db < 2; ++db) {
       const int cc = db * 4 + 2 * (G & 1) + (j >> 1);
@@ -177,9 +187,9 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     }
   }
 
-  f32x16 o[2];     // O^T accumulators: [dim block], this lane's query column
-  float m_ref;     // SAFE pass: reference maximum of the query column (log2 domain)
-  float l_run;     // this lane's share of the row sum
+  f32x16 o[2][2];  // O^T accumulators: [dim block][query half], this lane's query column
+  float m_ref[2];  // SAFE pass: reference maximum per query column (log2 domain)
+  float l_run[2];  // this lane's share of the row sums
 
   const bool dense = kv_idx == nullptr;
   const int count = dense ? nb : min(max(kv_cnt[rowid], 0), nb);
@@ -202,38 +212,37 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     const int J = __builtin_amdgcn_readlane(idx_cur, it & 63);
     return min(max(J, 0), nb - 1);
   };
-  // Direct-to-LDS load number i2 (0..7) of key tile J: even i2 moves 1 KB of the K tile into K
-  // buffer kb, odd i2 1 KB of the V tile into V buffer vb.  Rows of a ragged last tile that lie past
-  // the end of the head's buffer fail the hardware bounds check, which makes the load write zeros.
-  auto issue_part = [&](int J, int kb, int vb, int i2) {
+  // Direct-to-LDS load number i2 (0..7) of key tile J into buffer pair `buf`: even i2 moves 1 KB of
+  // the K tile, odd i2 1 KB of the V tile.  Rows of a ragged last tile that lie past the end of the
+  // head's buffer fail the hardware bounds check, which makes the load write zeros for them.
+  auto issue_part = [&](int J, int buf, int i2) {
     const int i = i2 >> 1;
     const bool is_v = (i2 & 1) != 0;
     const unsigned soff = static_cast<unsigned>(J) * TILE_BYTES;
-    const unsigned dst = smem_addr + wave * 1024 + NW * i * 1024 + (is_v ? V_BASE + vb * TILE_BYTES : kb * TILE_BYTES);
+    const unsigned dst = smem_addr + wave * 1024 + NW * i * 1024 + (is_v ? V_BASE : 0) + buf * TILE_BYTES;
     if (is_v) {
       dma16(vrsrc, voff, soff + i * NW * 1024, dst);
     } else {
       dma16(krsrc, koff[i % KN], soff + (i / KN) * KN * NW * 1024, dst);
     }
   };
-  auto issue = [&](int J, int kb, int vb) {
+  auto issue = [&](int J, int buf) {
 #pragma unroll
-    for (int i2 = 0; i2 < 8; ++i2) issue_part(J, kb, vb, i2);
+    for (int i2 = 0; i2 < 8; ++i2) issue_part(J, buf, i2);
   };
 
-  // K operands (A of S^T = K Q^T) of 32-key sub-tile u; kbase[c] = kaddr[c] + byte offset of the K buffer
-  auto read_k = [&](bf16x8 (&ka)[4], const unsigned (&kbase)[4], int u) {
+  // K operands (A of S^T = K Q^T) of the wave's 32-key sub-tile u; boff = byte offset of the buffer
+  auto read_k = [&](bf16x8 (&ka)[4], unsigned boff, int u) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c) ka[c] = *LDS_PTR(bf16x8, smem + kbase[(u & 1) ? (c ^ 2) : c] + u * 4096);
+    for (int c = 0; c < 4; ++c) ka[c] = *LDS_PTR(bf16x8, smem + boff + kaddr[(u & 1) ? (c ^ 2) : c] + u * 4096);
   };
-  // V^T operands (A of O^T += V^T P^T) of sub-tile u: [dim block][16-key chunk];
-  // vbase[db] = vaddr[db] + byte offset of the V buffer
-  auto read_v = [&](bf16x8 (&va)[2][2], const unsigned (&vbase)[2], int u) {
+  // V^T operands (A of O^T += V^T P^T) of sub-tile u: [dim block][16-key chunk]
+  auto read_v = [&](bf16x8 (&va)[2][2], unsigned boff, int u) {
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
       for (int cp = 0; cp < 2; ++cp) {
-        const unsigned char* p = smem + vbase[db] + (32 * u + 16 * cp) * 128;
+        const unsigned char* p = smem + boff + vaddr[db] + (32 * u + 16 * cp) * 128;
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
         const s16x4 hi =
             __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p + 8 * 128));
@@ -242,28 +251,20 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
         va[db][cp] = __builtin_bit_cast(bf16x8, av);
       }
   };
-  auto k_bases = [&](unsigned (&kbase)[4], int kb) {
-#pragma unroll
-    for (int c = 0; c < 4; ++c) kbase[c] = kaddr[c] + kb * TILE_BYTES;
-  };
-  auto v_bases = [&](unsigned (&vbase)[2], int vb) {
-#pragma unroll
-    for (int db = 0; db < 2; ++db) vbase[db] = vaddr[db] + vb * TILE_BYTES;
-  };
 
   const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
   // weights of key pair j (registers 2j, 2j+1) of a score block: exp2, round to bf16, add to the
   // row sum, store as word j of the two B operands
-  auto weigh_pair = [&](const f32x16& sc, u32x4 (&w)[2], int j) {
+  auto weigh_pair = [&](const f32x16& sc, u32x4 (&w)[2], float& lsum, int j) {
     const unsigned pk = pack_bf16(__builtin_amdgcn_exp2f(sc[2 * j]), __builtin_amdgcn_exp2f(sc[2 * j + 1]));
-    l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, l_run, false);
+    lsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, lsum, false);
     w[j >> 2][j & 3] = pk;
   };
 
   // ---------------------------------------------------------------------------------------------
-  // Plain tile loop: per 32-key sub-tile scores (4 MFMAs) -> weights -> O update (4 MFMAs), one
-  // barrier per tile, the next tile's loads in flight meanwhile.  Used for the SAFE pass and for
-  // block 64.
+  // Plain tile loop: per (32-key sub-tile, query half) scores (4 MFMAs) -> weights -> O update
+  // (4 MFMAs), one barrier per tile, the next tile's loads in flight meanwhile.  Used for the SAFE
+  // pass and for block 64.
   //   SAFE = true: online softmax.  The accumulator of the score MFMA starts at -m_ref, so the MFMA
   //   result is already relative to the reference, and m_ref is raised only when a sub-tile exceeds
   //   it by more than 2^kRaise.  Keys of the ragged last tile that lie past the end are masked.
@@ -273,65 +274,66 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     constexpr bool SAFE = decltype(safec)::value;
     if (count <= 0) return;
     int J_cur = block_at(0);
-    issue(J_cur, 0, 0);
+    issue(J_cur, 0);
     for (int it = 0; it < count; ++it) {
-      const int buf = it & 1;  // this loop uses K buffer and V buffer number it % 2
+      const int buf = it & 1;
       const int J_next = (it + 1 < count) ? block_at(it + 1) : 0;
       __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile `it` has landed
-      __syncthreads();                     // ... and so has everyone else's; buffers buf^1 are free
-      if (it + 1 < count) issue(J_next, buf ^ 1, buf ^ 1);
-      unsigned kbase[4], vbase[2];
-      k_bases(kbase, buf);
-      v_bases(vbase, buf);
+      __syncthreads();                     // ... and so has everyone else's; buffer buf^1 is free
+      if (it + 1 < count) issue(J_next, buf ^ 1);
+      const unsigned boff = buf * TILE_BYTES;
       const bool ragged = (J_cur == nb - 1 && tail < B);
       if (ragged && !SAFE) pad_keys += B - tail;
 #pragma unroll
-      for (int u = 0; u < NU; ++u) {
+      for (int u = 0; u < NH; ++u) {
         bf16x8 ka[4], va[2][2];
-        read_k(ka, kbase, u);
-        read_v(va, vbase, u);
-        const float base = (SAFE && m_ref != -INFINITY) ? m_ref : 0.f;
-        f32x16 sc;
+        read_k(ka, boff, u);
+        read_v(va, boff, u);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sc[i] = -base;
+        for (int b2 = 0; b2 < 2; ++b2) {
+          const float base = (SAFE && m_ref[b2] != -INFINITY) ? m_ref[b2] : 0.f;
+          f32x16 sc;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c], qf[c], sc, 0, 0, 0);
-        if constexpr (SAFE) {
-          if (ragged) {
+          for (int i = 0; i < 16; ++i) sc[i] = -base;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const int key = u * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-              if (key >= tail) sc[i] = -INFINITY;
+          for (int c = 0; c < 4; ++c) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c], qf[b2][c], sc, 0, 0, 0);
+          if constexpr (SAFE) {
+            if (ragged) {
+#pragma unroll
+              for (int i = 0; i < 16; ++i) {
+                const int key = kh * KW + u * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
+                if (key >= tail) sc[i] = -INFINITY;
+              }
+            }
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sc[i]);
+            tmax = fmaxf(tmax, xor32(tmax));
+            const bool unset = m_ref[b2] == -INFINITY;
+            const bool raise = unset ? (tmax > -INFINITY) : (tmax > kRaise);
+            if (__any(raise)) {  // rare after the first tile
+              const float shift = raise ? tmax : 0.f;
+              const float alpha = unset ? 1.f : exp2f(-shift);  // nothing accumulated yet while unset
+              if (raise) m_ref[b2] = base + shift;
+              l_run[b2] *= alpha;
+#pragma unroll
+              for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[db][b2][i] *= alpha;
+#pragma unroll
+              for (int i = 0; i < 16; ++i) sc[i] -= shift;
             }
           }
-          float tmax = -INFINITY;
+          u32x4 w[2];
 #pragma unroll
-          for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sc[i]);
-          tmax = fmaxf(tmax, xor32(tmax));
-          const bool unset = m_ref == -INFINITY;
-          const bool raise = unset ? (tmax > -INFINITY) : (tmax > kRaise);
-          if (__any(raise)) {  // rare after the first tile
-            const float shift = raise ? tmax : 0.f;
-            const float alpha = unset ? 1.f : exp2f(-shift);  // nothing accumulated yet while unset
-            if (raise) m_ref = base + shift;
-            l_run *= alpha;
+          for (int j = 0; j < 8; ++j) weigh_pair(sc, w, l_run[b2], j);
 #pragma unroll
-            for (int db = 0; db < 2; ++db)
+          for (int db = 0; db < 2; ++db)
 #pragma unroll
-              for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sc[i] -= shift;
-          }
+            for (int cp = 0; cp < 2; ++cp)
+              o[db][b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db][cp], __builtin_bit_cast(bf16x8, w[cp]),
+                                                                  o[db][b2], 0, 0, 0);
         }
-        u32x4 w[2];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) weigh_pair(sc, w, j);
-#pragma unroll
-        for (int db = 0; db < 2; ++db)
-#pragma unroll
-          for (int cp = 0; cp < 2; ++cp)
-            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db][cp], __builtin_bit_cast(bf16x8, w[cp]), o[db], 0,
-                                                            0, 0);
       }
       J_cur = J_next;
     }
@@ -339,23 +341,22 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
 
   // ---------------------------------------------------------------------------------------------
   // Fast pass for block 128: the same arithmetic as plain_loop<SAFE = false>, software pipelined
-  // inside the wave.  Unit n of a tile is its 32-key sub-tile n (0..3): scores QK(n) (4 MFMAs into
-  // 16 registers), weights W(n) (16 exp2, 8 packs, 8 dot2), O update PV(n) (4 MFMAs).  While the
-  // VALU works on W(n) the matrix pipe gets QK(n+1) and PV(n-1), one MFMA per four VALU
-  // instructions, so the wave's VALU and MFMA streams overlap instead of waiting for each other.
-  // LDS operands are fetched a whole unit ahead of their use, into alternating register sets: K of
-  // unit n+2 and V of unit n at the start of unit n.  Tile T lives in K buffer T%2 and V buffer T%3.
-  // The workgroup synchronises once per tile, at the start of unit 2: by then every K read of the
-  // tile has been issued and tile T+1 has landed, so the first K operands of tile T+1 are read right
-  // away and the loads of tile T+2 are started (K into the buffer just vacated, V into the buffer of
-  // tile T-1), one after each of the following MFMAs: a full tile ahead of their use.
+  // inside the wave.  A unit is (32-key sub-tile u, query half b): scores QK (4 MFMAs into 16
+  // registers), weights W (16 exp2, 8 packs, 8 dot2), O update PV (4 MFMAs).  A tile has four units
+  // n = 0..3 = (u0,b0), (u0,b1), (u1,b0), (u1,b1).  While the VALU works on W(n) the matrix pipe gets
+  // QK(n+1) and PV(n-1), one MFMA per four VALU instructions, so the wave's VALU and MFMA streams
+  // overlap instead of waiting for each other.  K operands of a sub-tile serve two units, V operands
+  // likewise; they are fetched from LDS at least half a unit ahead of their first use.  By the end
+  // of unit 1 every LDS read of the tile has been issued, so at the start of unit 2 the workgroup
+  // synchronises once: the next tile is known to have landed (its first K operands are read right
+  // after the last score MFMA of this tile) and the current buffers are free, so the eight loads of
+  // the tile after next are issued into them, one after each of the following MFMAs.
   auto fast_loop = [&](int& pad_keys) {
     if (count <= 0) return;
-    f32x16 sc[2];        // scores: [unit parity]
-    u32x4 pw[2][2];      // weights as packed bf16 pairs: [unit parity][16-key chunk]
-    bf16x8 ka[2][4];     // K operands: [unit parity][16-dim chunk]
-    bf16x8 va[2][2][2];  // V^T operands: [unit parity][dim block][16-key chunk]
-    unsigned kbase[4], knext[4], vbase[2];  // LDS addresses of this tile's K, the next tile's K, this tile's V
+    f32x16 sc[2];        // scores: [query half]
+    u32x4 pw[2][2];      // weights as packed bf16 pairs: [query half][16-key chunk]
+    bf16x8 ka[4];        // K operands of the sub-tile whose scores are computed next
+    bf16x8 va[2][2][2];  // V^T operands: [sub-tile][dim block][16-key chunk]
 #pragma unroll
     for (int cp = 0; cp < 2; ++cp) {
       pw[1][cp] = u32x4{0u, 0u, 0u, 0u};
@@ -363,11 +364,15 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
       for (int db = 0; db < 2; ++db) va[1][db][cp] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
     }
 
-    // one unit: U = its number in the tile, P = U & 1 the parity of its registers, Q the other one.
-    // Slots 0..3: MFMA of QK(U+1) (if do_qk) + one weight pair; slots 4..7: MFMA of PV(U-1) + one
-    // weight pair.  mid(slot) places LDS reads, the barrier and loads after that slot's MFMA.
-    auto unit = [&](auto uc, auto doqkc, auto&& mid) {
-      constexpr int U = decltype(uc)::value, P = U & 1, Q = P ^ 1;
+    // one unit N = (sub-tile N/2, query half N%2).  Slots 0..3: MFMA of QK(N+1) (if do_qk) + one
+    // weight pair; slots 4..7: MFMA of PV(N-1) + one weight pair.  mid(slot) places LDS reads, the
+    // barrier and loads after that slot's MFMA.
+    auto unit = [&](auto nc, auto doqkc, auto&& mid) {
+      constexpr int N = decltype(nc)::value;
+      constexpr int BQ = N & 1;                 // query half whose weights are computed
+      constexpr int BN = (N + 1) & 1;           // query half of QK(N+1)
+      constexpr int BP = (N + 3) & 1;           // query half of PV(N-1)
+      constexpr int UP = ((N + 3) & 3) >> 1;    // sub-tile of PV(N-1)
       constexpr bool do_qk = decltype(doqkc)::value;
 #define BSGA_SLOT(S_)                                                                                          \
   {                                                                                                            \
@@ -375,17 +380,17 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
       if constexpr (do_qk) {                                                                                   \
         if constexpr ((S_) == 0) {                                                                             \
           const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}; \
-          sc[Q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[Q][0], qf[0], zero, 0, 0, 0);                     \
+          sc[BN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qf[BN][0], zero, 0, 0, 0);                   \
         } else {                                                                                               \
-          sc[Q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[Q][(S_) & 3], qf[(S_) & 3], sc[Q], 0, 0, 0);       \
+          sc[BN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[(S_) & 3], qf[BN][(S_) & 3], sc[BN], 0, 0, 0);    \
         }                                                                                                      \
       }                                                                                                        \
     } else {                                                                                                   \
-      o[((S_) >> 1) & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[Q][((S_) >> 1) & 1][(S_) & 1],            \
-                                                                 __builtin_bit_cast(bf16x8, pw[Q][(S_) & 1]),  \
-                                                                 o[((S_) >> 1) & 1], 0, 0, 0);                 \
+      o[((S_) >> 1) & 1][BP] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                        \
+          va[UP][((S_) >> 1) & 1][(S_) & 1], __builtin_bit_cast(bf16x8, pw[BP][(S_) & 1]), o[((S_) >> 1) & 1][BP], 0, \
+          0, 0);                                                                                               \
     }                                                                                                          \
-    weigh_pair(sc[P], pw[P], (S_));                                                                            \
+    weigh_pair(sc[BQ], pw[BQ], l_run[BQ], (S_));                                                               \
     mid(Int<(S_)>{});                                                                                          \
     __builtin_amdgcn_sched_barrier(0);                                                                         \
   }
@@ -393,140 +398,174 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
 #undef BSGA_SLOT
     };
 
-    // a whole tile T (K buffer kb = T%2, V buffer vb = T%3; the tile after next goes to kb and vb2).
-    // On entry: sc[0] = QK(0) of this tile, ka[1] = K operands of unit 1, pw[1] / va[1] = weights /
+    // a whole tile in buffer pair `buf` (byte offset boff; the other pair is at boff ^ TILE_BYTES).
+    // On entry: sc[0] = QK(0) of this tile, ka = K operands of sub-tile 0, pw[1] / va[1] = weights /
     // V operands of the previous tile's unit 3 (zeros before the first tile).
-    auto tile = [&](auto hasnextc, int J, int J_next2, int kb, int vb, int vb2) {
+    auto tile = [&](auto hasnextc, int J, int J_next2, int buf) {
       constexpr bool has_next = decltype(hasnextc)::value;
       if (J == nb - 1 && tail < B) pad_keys += B - tail;
-      k_bases(kbase, kb);
-      k_bases(knext, kb ^ 1);
-      v_bases(vbase, vb);
-      unit(Int<0>{}, std::true_type{}, [&](auto slot) {  // QK(1); PV(previous unit 3)
+      const unsigned boff = buf * TILE_BYTES;
+      unit(Int<0>{}, std::true_type{}, [&](auto slot) {  // QK(1); K(u1); PV(previous 3); V(u0)
         constexpr int S = decltype(slot)::value;
-        if constexpr (S == 0) read_k(ka[0], kbase, 2);
-        if constexpr (S == 1) read_v(va[0], vbase, 0);
+        if constexpr (S == 0) read_v(va[0], boff, 0);
+        if constexpr (S == 3) read_k(ka, boff, 1);
       });
-      unit(Int<1>{}, std::true_type{}, [&](auto slot) {  // QK(2); PV(0)
+      unit(Int<1>{}, std::true_type{}, [&](auto slot) {  // QK(2); PV(0); V(u1)
         constexpr int S = decltype(slot)::value;
-        if constexpr (S == 0) read_k(ka[1], kbase, 3);
-        if constexpr (S == 1) read_v(va[1], vbase, 1);
+        if constexpr (S == 0) read_v(va[1], boff, 1);
       });
-      unit(Int<2>{}, std::true_type{}, [&](auto slot) {  // QK(3); synchronise; PV(1) + loads 0..3
+      unit(Int<2>{}, std::true_type{}, [&](auto slot) {  // synchronise; QK(3); K(next tile u0); PV(1) + loads 0..3
         constexpr int S = decltype(slot)::value;
         if constexpr (S == 0) {
           __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of the next tile has landed
-          __syncthreads();                     // every K read of this tile, every read of the previous one, is complete
-          if constexpr (has_next) read_k(ka[0], knext, 0);
+          __syncthreads();                     // every read of this tile is complete in every wave
         }
-        if constexpr (S == 1) read_v(va[0], vbase, 2);
-        if constexpr (S >= 4) issue_part(J_next2, kb, vb2, S - 4);
+        if constexpr (S == 3 && has_next) read_k(ka, boff ^ TILE_BYTES, 0);
+        if constexpr (S >= 4) issue_part(J_next2, buf, S - 4);
       });
       unit(Int<3>{}, hasnextc, [&](auto slot) {  // QK(next tile's unit 0); PV(2) + loads 4..7
         constexpr int S = decltype(slot)::value;
-        if constexpr (S == 0 && has_next) read_k(ka[1], knext, 1);
-        if constexpr (S == 1) read_v(va[1], vbase, 3);
-        if constexpr (S >= 4) issue_part(J_next2, kb, vb2, S);
+        if constexpr (S >= 4) issue_part(J_next2, buf, S);
       });
     };
 
-    // ---- prologue: tiles 0 and 1 on their way, QK(0), K operands of unit 1 -------------------------
+    // ---- prologue: tiles 0 and 1 on their way, K operands of sub-tile 0, QK(0) ----------------------
     int J_cur = block_at(0);
-    issue(J_cur, 0, 0);
+    issue(J_cur, 0);
     int J_nxt = J_cur;
     if (count > 1) {
       J_nxt = block_at(1);
-      issue(J_nxt, 1, 1);
+      issue(J_nxt, 1);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
-    k_bases(kbase, 0);
-    read_k(ka[0], kbase, 0);
+    read_k(ka, 0u, 0);
     {
       const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0][0], qf[0], zero, 0, 0, 0);
+      sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qf[0][0], zero, 0, 0, 0);
 #pragma unroll
-      for (int c = 1; c < 4; ++c) sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0][c], qf[c], sc[0], 0, 0, 0);
+      for (int c = 1; c < 4; ++c) sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c], qf[0][c], sc[0], 0, 0, 0);
     }
-    read_k(ka[1], kbase, 1);
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- all tiles but the last --------------------------------------------------------------------
-    int vb = 0;
     for (int T = 0; T + 1 < count; ++T) {
       // the tile after next; at the end of the list one more (harmless) load of a valid tile
       const int J2 = (T + 2 < count) ? block_at(T + 2) : J_cur;
-      const int vb2 = (vb == 0) ? 2 : vb - 1;  // (T + 2) % 3 == (T - 1) % 3
-      tile(std::true_type{}, J_cur, J2, T & 1, vb, vb2);
+      tile(std::true_type{}, J_cur, J2, T & 1);
       J_cur = J_nxt;
       J_nxt = J2;
-      vb = (vb == 2) ? 0 : vb + 1;
     }
     // ---- the last tile, then the O update of its last unit -----------------------------------------
-    tile(std::false_type{}, J_cur, J_cur, (count - 1) & 1, vb, (vb == 0) ? 2 : vb - 1);
+    tile(std::false_type{}, J_cur, J_cur, (count - 1) & 1);
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
       for (int cp = 0; cp < 2; ++cp)
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[1][db][cp], __builtin_bit_cast(bf16x8, pw[1][cp]), o[db], 0,
-                                                        0, 0);
+        o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[1][db][cp], __builtin_bit_cast(bf16x8, pw[1][cp]),
+                                                           o[db][1], 0, 0, 0);
   };
 
-  // A whole pass over the row's key tiles, then the output.  Returns true (to every thread of the
-  // workgroup) if the fast pass must be repeated in SAFE mode because a row sum or an output left
-  // the range in which reference-free weights are trustworthy: a weight 2^s overflows for s >= 128
-  // (the row sum then exceeds the upper limit, or O is not finite), and weights below 2^-126 flush
-  // to zero, which is harmless as long as the row sum is at least 2^-80 (at most 2^24 keys x 2^-126
-  // lost: a relative error under 2^-22).
+  // A whole pass over the row's key tiles, then the merge of the two key halves (wave (qi, 1) parks
+  // its state in LDS as [qi][68 values][64 lanes] and wave (qi, 0) folds it in) and the output.
+  // Returns true (to every thread of the workgroup) if the fast pass must be repeated in SAFE mode
+  // because a row sum or an output left the range in which reference-free weights are trustworthy:
+  // a weight 2^s overflows for s >= 128 (the row sum then exceeds the upper limit, or O is not
+  // finite), and weights below 2^-126 flush to zero, which is harmless as long as the row sum is at
+  // least 2^-80 (at most 2^24 keys x 2^-126 lost: a relative error under 2^-22).
   auto pass = [&](auto safec) -> bool {
     constexpr bool SAFE = decltype(safec)::value;
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
-    m_ref = -INFINITY;
-    l_run = 0.f;
+      for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][b2][i] = 0.f;
+    m_ref[0] = m_ref[1] = -INFINITY;
+    l_run[0] = l_run[1] = 0.f;
     idx_cur = load_idx(0);
     idx_next = load_idx(64);
     int pad_keys = 0;  // zero-filled keys past the end that the fast pass has summed as weight 1
     if constexpr (!SAFE && B == 128) fast_loop(pad_keys);
     else plain_loop(safec, pad_keys);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // no direct-to-LDS load may still be in flight
+    __syncthreads();                     // ... in any wave: LDS can be reused
 
-    float l = l_run + xor32(l_run);
-    if constexpr (!SAFE) {
-      l -= static_cast<float>(pad_keys);
-      bool bad = !(l >= 0x1p-80f && l <= 0x1p100f);
+    float* park = reinterpret_cast<float*>(smem) + 16 + qi * 68 * 64;
+    if (kh == 1) {
 #pragma unroll
       for (int db = 0; db < 2; ++db)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) bad = bad || !(fabsf(o[db][i]) < INFINITY);
+        for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) park[((db * 2 + b2) * 16 + i) * 64 + lane] = o[db][b2][i];
+#pragma unroll
+      for (int b2 = 0; b2 < 2; ++b2) {
+        park[(64 + b2) * 64 + lane] = m_ref[b2];
+        park[(66 + b2) * 64 + lane] = l_run[b2];
+      }
+    }
+    volatile int* flag = reinterpret_cast<volatile int*>(smem);  // workgroup-wide OR of `bad`
+    if (tid == 0) *flag = 0;
+    __syncthreads();
+    bool bad = false;
+    float lt[2], mt[2];
+    if (kh == 0) {
+#pragma unroll
+      for (int b2 = 0; b2 < 2; ++b2) {
+        const float l1 = park[(66 + b2) * 64 + lane];
+        float a0 = 1.f, a1 = 1.f;
+        mt[b2] = 0.f;
+        if constexpr (SAFE) {
+          const float m1 = park[(64 + b2) * 64 + lane];
+          const float m0 = m_ref[b2];
+          mt[b2] = fmaxf(m0, m1);
+          const float mu = (mt[b2] == -INFINITY) ? 0.f : mt[b2];
+          a0 = exp2f(m0 - mu);  // exp2f(-inf) = 0 for a half that saw nothing
+          a1 = exp2f(m1 - mu);
+        }
+        float l = l_run[b2] * a0 + l1 * a1;
+        l += xor32(l);
+        if constexpr (!SAFE) {
+          l -= static_cast<float>(pad_keys);
+          bad = bad || !(l >= 0x1p-80f && l <= 0x1p100f);
+        }
+        lt[b2] = l;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            o[db][b2][i] = o[db][b2][i] * a0 + park[((db * 2 + b2) * 16 + i) * 64 + lane] * a1;
+            if constexpr (!SAFE) bad = bad || !(fabsf(o[db][b2][i]) < INFINITY);
+          }
+      }
+    }
+    if constexpr (!SAFE) {
       if (count <= 0) bad = false;  // an empty row is zeros by definition, not a range problem
-      // workgroup-wide OR through one LDS word (the tile buffers are idle by now)
-      volatile int* flag = reinterpret_cast<volatile int*>(smem);
-      __syncthreads();
-      if (tid == 0) *flag = 0;
-      __syncthreads();
       if (bad) *flag = 1;
       __syncthreads();
       const bool any_bad = *flag != 0;
       __syncthreads();
       if (any_bad) return true;
     }
-    const float inv = l > 0.f ? 1.f / l : 0.f;
-    if (qrow < n_tokens) {
+    if (kh == 0) {
 #pragma unroll
-      for (int db = 0; db < 2; ++db)
+      for (int b2 = 0; b2 < 2; ++b2) {
+        const float inv = lt[b2] > 0.f ? 1.f / lt[b2] : 0.f;
+        const int64_t row = int64_t(I) * B + qi * 64 + b2 * 32 + n;
+        if (row < n_tokens) {
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const f32x16& x = o[db];
-          const int i = 4 * r4;
-          const u32x2 w = {pack_bf16(x[i] * inv, x[i + 1] * inv), pack_bf16(x[i + 2] * inv, x[i + 3] * inv)};
-          *reinterpret_cast<u32x2*>(out + (int64_t(h) * n_tokens + qrow) * kD + db * 32 + 8 * r4 + 4 * g) = w;
+          for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+              const f32x16& x = o[db][b2];
+              const int i = 4 * r4;
+              const u32x2 w = {pack_bf16(x[i] * inv, x[i + 1] * inv), pack_bf16(x[i + 2] * inv, x[i + 3] * inv)};
+              *reinterpret_cast<u32x2*>(out + (int64_t(h) * n_tokens + row) * kD + db * 32 + 8 * r4 + 4 * g) = w;
+            }
+          if (lse != nullptr && g == 0)
+            lse[int64_t(h) * n_tokens + row] = lt[b2] > 0.f ? (mt[b2] + log2f(lt[b2])) * kLn2 : -INFINITY;
         }
-      if (lse != nullptr && g == 0) {
-        const float mref = (SAFE && m_ref != -INFINITY) ? m_ref : 0.f;
-        lse[int64_t(h) * n_tokens + qrow] = l > 0.f ? (mref + log2f(l)) * kLn2 : -INFINITY;
       }
     }
     return false;
@@ -550,27 +589,21 @@ int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int
   const unsigned char* kp = static_cast<const unsigned char*>(k);
   const unsigned char* vp = static_cast<const unsigned char*>(v);
   unsigned short* op = static_cast<unsigned short*>(out);
+  // LDS: two K and two V tile buffers (64 KB for block 128); block 64 also needs room for the
+  // parked accumulators of the end merge (17 KB + 64 B), which 32 KB covers
+  const size_t lds64 = 4 * 64 * 128, lds128 = 4 * 128 * 128;
   if (getenv("BSGA_DEBUG") != nullptr) {
     int n64 = -1, n128 = -1;
-    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n64, attn_bf16_kernel<64>, 128, 5 * 64 * 128);
-    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n128, attn_bf16_kernel<128>, 256, 5 * 128 * 128);
+    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n64, attn_bf16_kernel<64>, 128, lds64);
+    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n128, attn_bf16_kernel<128>, 256, lds128);
     fprintf(stderr, "[bsga] attention occupancy (workgroups per CU): block 64 -> %d, block 128 -> %d\n", n64, n128);
   }
-  // 5 tile buffers (2 K + 3 V): 80 KB for block 128, above the 64 KB a kernel gets without asking
-  static bool lds_limit_raised = false;
-  if (!lds_limit_raised) {
-    if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<128>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 5 * 128 * 128),
-                           "bsga bf16 attention: raising the dynamic LDS limit"))
-      return rc;
-    lds_limit_raised = true;
-  }
   if (block == 64) {
-    hipLaunchKernelGGL((attn_bf16_kernel<64>), grid, dim3(128), 5 * 64 * 128, stream, qp, kp, vp, op, lse, kv_idx,
-                       kv_cnt, idx_stride, n_tokens, nb, scale_log2);
+    hipLaunchKernelGGL((attn_bf16_kernel<64>), grid, dim3(128), lds64, stream, qp, kp, vp, op, lse, kv_idx, kv_cnt,
+                       idx_stride, n_tokens, nb, scale_log2);
   } else {
-    hipLaunchKernelGGL((attn_bf16_kernel<128>), grid, dim3(256), 5 * 128 * 128, stream, qp, kp, vp, op, lse, kv_idx,
-                       kv_cnt, idx_stride, n_tokens, nb, scale_log2);
+    hipLaunchKernelGGL((attn_bf16_kernel<128>), grid, dim3(256), lds128, stream, qp, kp, vp, op, lse, kv_idx, kv_cnt,
+                       idx_stride, n_tokens, nb, scale_log2);
   }
   return check_hip(hipGetLastError(), "bsga bf16 attention launch");
 }
