@@ -357,6 +357,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     u32x4 pw[2][2];      // weights as packed bf16 pairs: [query half][16-key chunk]
     bf16x8 ka[4];        // K operands of the sub-tile whose scores are computed next
     bf16x8 va[2][2][2];  // V^T operands: [sub-tile][dim block][16-key chunk]
+    float ex[2][2];      // exponentiated scores of the key pair that is packed in the next slot
 #pragma unroll
     for (int cp = 0; cp < 2; ++cp) {
       pw[1][cp] = u32x4{0u, 0u, 0u, 0u};
@@ -390,7 +391,21 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
           va[UP][((S_) >> 1) & 1][(S_) & 1], __builtin_bit_cast(bf16x8, pw[BP][(S_) & 1]), o[((S_) >> 1) & 1][BP], 0, \
           0, 0);                                                                                               \
     }                                                                                                          \
-    weigh_pair(sc[BQ], pw[BQ], l_run[BQ], (S_));                                                               \
+    /* weights, staggered by one slot so that no instruction waits for the one just before it:   */          \
+    /* pack pair S_ (exponentiated in the previous slot), exponentiate the next pair, then sum.  */          \
+    {                                                                                                          \
+      const unsigned pk = pack_bf16(ex[(S_) & 1][0], ex[(S_) & 1][1]);                                         \
+      if constexpr ((S_) < 7) {                                                                                \
+        ex[((S_) + 1) & 1][0] = __builtin_amdgcn_exp2f(sc[BQ][2 * (S_) + 2]);                                  \
+        ex[((S_) + 1) & 1][1] = __builtin_amdgcn_exp2f(sc[BQ][2 * (S_) + 3]);                                  \
+      } else {                                                                                                 \
+        ex[0][0] = __builtin_amdgcn_exp2f(sc[BN][0]);                                                          \
+        ex[0][1] = __builtin_amdgcn_exp2f(sc[BN][1]);                                                          \
+      }                                                                                                        \
+      __builtin_amdgcn_sched_barrier(0);                                                                       \
+      l_run[BQ] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, l_run[BQ], false);     \
+      pw[BQ][(S_) >> 2][(S_) & 3] = pk;                                                                        \
+    }                                                                                                          \
     mid(Int<(S_)>{});                                                                                          \
     __builtin_amdgcn_sched_barrier(0);                                                                         \
   }
@@ -446,6 +461,8 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
 #pragma unroll
       for (int c = 1; c < 4; ++c) sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c], qf[0][c], sc[0], 0, 0, 0);
     }
+    ex[0][0] = __builtin_amdgcn_exp2f(sc[0][0]);
+    ex[0][1] = __builtin_amdgcn_exp2f(sc[0][1]);
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- all tiles but the last --------------------------------------------------------------------
