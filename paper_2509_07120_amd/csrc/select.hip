@@ -1,15 +1,17 @@
 // Block scores, block softmax and block selection (Sec. 4.1, "Predicting Block Masks" and
 // "Selecting Blocks"), all in float64.
 //
-// One workgroup of 256 threads per (head, query block) row:
-//   1. logits[J] = scale * <q_pool[I], k_pool[J]>   four lanes share one J (16 dims each)
+// One workgroup of 256 threads handles R consecutive query-block rows of one head:
+//   1. logits[r][J] = scale * <q_pool[I+r], k_pool[J]>  four lanes share one J (16 dims each); every
+//      k_pool element is loaded once and used for all R rows (k_pool of a head is re-read by every
+//      workgroup from L2, which is what bounds this kernel, hence R rows per workgroup)
+// then, row by row:
 //   2. p = softmax(logits)                          block-wide max and sum
 //   3. rank: bitonic sort in LDS by (p descending, J ascending)
 //   4. inclusive scan of p in rank order; n_cdf = 1 + first rank whose running sum reaches tau
 //   5. keep the first n = min(nb_k, max(n_cdf, k, 1)) ranks, OR the forced rows/columns in
 //   6. emit bit mask words, the ascending index list and the count
-// The row of k_pool for a head (nb_k x 512 B) is re-read by every row's workgroup and is served
-// from L2; nothing but the outputs goes to HBM.
+// Nothing but the outputs goes to HBM.
 #include "bsga_internal.h"
 
 namespace bsga {
@@ -35,60 +37,77 @@ __device__ inline bool ranks_before(double pa, int ia, double pb, int ib) {
   return pa > pb || (pa == pb && ia < ib);
 }
 
+template <int R>
 __global__ __launch_bounds__(kThreads) void select_kernel(
     const double* __restrict__ q_pool, const double* __restrict__ k_pool, int nb_q, int nb_k, int nbp,
     double score_scale, double tau, int k_floor, const uint8_t* __restrict__ force_q,
     const uint8_t* __restrict__ force_k, uint32_t* __restrict__ mask_bits, int32_t* __restrict__ kv_idx,
     int32_t* __restrict__ kv_cnt, int idx_stride) {
   extern __shared__ __align__(16) unsigned char smem[];
-  double* val = reinterpret_cast<double*>(smem);                 // [nbp] logits -> p -> sorted p
-  int* idx = reinterpret_cast<int*>(smem + size_t(nbp) * 8);     // [nbp] block index per rank; later keep flags
+  double* val = reinterpret_cast<double*>(smem);                 // [nbp] p of the current row -> sorted p
+  int* idx = reinterpret_cast<int*>(smem + size_t(nbp) * 8);     // [nbp] block index per rank
+  double* logit = reinterpret_cast<double*>(smem + size_t(nbp) * 12);  // [R][nb_k] logits of all rows
   __shared__ double red[kWaves];
   __shared__ double red2[kWaves];
   __shared__ int wave_cnt[kWaves];
   __shared__ int first_rank;
 
-  const int I = blockIdx.x;
+  const int I0 = blockIdx.x * R;
   const int h = blockIdx.y;
   const int t = threadIdx.x;
   const int lane = t & 63;
   const int wave = t >> 6;
 
-  // ---- 1. logits ------------------------------------------------------------------------
+  // ---- 1. logits of R rows ----------------------------------------------------------------------
   // lane quarter qd of a group of four handles the 16-byte chunks qd, qd+4, ..., qd+28 of a row
   const int qd = t & 3;
-  const double2* qrow = reinterpret_cast<const double2*>(q_pool + (int64_t(h) * nb_q + I) * kD);
-  double2 qv[8];
+  double2 qv[R][8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) qv[i] = qrow[4 * i + qd];
+  for (int r = 0; r < R; ++r) {
+    const int I = min(I0 + r, nb_q - 1);  // rows past the end repeat the last row and are not emitted
+    const double2* qrow = reinterpret_cast<const double2*>(q_pool + (int64_t(h) * nb_q + I) * kD);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) qv[r][i] = qrow[4 * i + qd];
+  }
   const double2* kbase = reinterpret_cast<const double2*>(k_pool + int64_t(h) * nb_k * kD);
   for (int j0 = 0; j0 < nb_k; j0 += kThreads / 4) {
     const int J = j0 + (t >> 2);
-    double acc = 0.0;
+    double acc[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) acc[r] = 0.0;
     if (J < nb_k) {
       const double2* krow = kbase + int64_t(J) * (kD / 2);
       double2 kv[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) kv[i] = krow[4 * i + qd];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) acc = fma(qv[i].x, kv[i].x, fma(qv[i].y, kv[i].y, acc));
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[r] = fma(qv[r][i].x, kv[i].x, fma(qv[r][i].y, kv[i].y, acc[r]));
     }
-    acc += __shfl_xor(acc, 1);
-    acc += __shfl_xor(acc, 2);
-    if (qd == 0 && J < nb_k) val[J] = score_scale * acc;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      acc[r] += __shfl_xor(acc[r], 1);
+      acc[r] += __shfl_xor(acc[r], 2);
+      if (qd == 0 && J < nb_k) logit[r * nb_k + J] = score_scale * acc[r];
+    }
   }
   __syncthreads();
 
+  for (int rr = 0; rr < R; ++rr) {
+  const int I = I0 + rr;
+  if (I >= nb_q) break;  // uniform
+  const double* lrow = logit + rr * nb_k;
   // ---- 2. softmax -------------------------------------------------------------------------
   double m = -INFINITY;
-  for (int J = t; J < nb_k; J += kThreads) m = fmax(m, val[J]);
+  for (int J = t; J < nb_k; J += kThreads) m = fmax(m, lrow[J]);
   m = wave_max(m);
   if (lane == 0) red[wave] = m;
   __syncthreads();
   m = fmax(fmax(red[0], red[1]), fmax(red[2], red[3]));
   double z = 0.0;
   for (int J = t; J < nb_k; J += kThreads) {
-    const double e = exp(val[J] - m);
+    const double e = exp(lrow[J] - m);
     val[J] = e;
     z += e;
   }
@@ -187,6 +206,25 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     __syncthreads();
   }
   if (t == 0 && kv_cnt != nullptr) kv_cnt[row] = running;
+  __syncthreads();  // val / idx / first_rank are reused by the next row
+  }
+}
+
+template <int R>
+static int launch_rows(const double* q_pool, const double* k_pool, int heads, int nb_q, int nb_k, int nbp,
+                       size_t smem, double score_scale, double tau, int k_floor, const uint8_t* force_q,
+                       const uint8_t* force_k, uint32_t* mask_bits, int32_t* kv_idx, int32_t* kv_cnt, int idx_stride,
+                       hipStream_t stream) {
+  if (smem > 64 * 1024) {
+    if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<R>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem)),
+                           "bsga_select_blocks: raising the dynamic LDS limit"))
+      return rc;
+  }
+  dim3 grid((nb_q + R - 1) / R, heads), blk(kThreads);
+  hipLaunchKernelGGL(select_kernel<R>, grid, blk, smem, stream, q_pool, k_pool, nb_q, nb_k, nbp, score_scale, tau,
+                     k_floor, force_q, force_k, mask_bits, kv_idx, kv_cnt, idx_stride);
+  return check_hip(hipGetLastError(), "bsga_select_blocks launch");
 }
 
 }  // namespace
@@ -196,11 +234,16 @@ int launch_select(const double* q_pool, const double* k_pool, int heads, int nb_
                   int32_t* kv_idx, int32_t* kv_cnt, int idx_stride, hipStream_t stream) {
   int nbp = kThreads;
   while (nbp < nb_k) nbp <<= 1;
-  const size_t smem = size_t(nbp) * (sizeof(double) + sizeof(int));
-  dim3 grid(nb_q, heads), blk(kThreads);
-  hipLaunchKernelGGL(select_kernel, grid, blk, smem, stream, q_pool, k_pool, nb_q, nb_k, nbp, score_scale, tau,
-                     k_floor, force_q, force_k, mask_bits, kv_idx, kv_cnt, idx_stride);
-  return check_hip(hipGetLastError(), "bsga_select_blocks launch");
+  // LDS: sort arrays (12 bytes per padded rank) + R rows of logits; up to 96 KB so two workgroups fit a CU
+  auto bytes = [&](int rows) { return size_t(nbp) * 12 + size_t(rows) * nb_k * 8; };
+  if (nb_q >= 4 && bytes(4) <= 96 * 1024)
+    return launch_rows<4>(q_pool, k_pool, heads, nb_q, nb_k, nbp, bytes(4), score_scale, tau, k_floor, force_q,
+                          force_k, mask_bits, kv_idx, kv_cnt, idx_stride, stream);
+  if (nb_q >= 2 && bytes(2) <= 96 * 1024)
+    return launch_rows<2>(q_pool, k_pool, heads, nb_q, nb_k, nbp, bytes(2), score_scale, tau, k_floor, force_q,
+                          force_k, mask_bits, kv_idx, kv_cnt, idx_stride, stream);
+  return launch_rows<1>(q_pool, k_pool, heads, nb_q, nb_k, nbp, bytes(1), score_scale, tau, k_floor, force_q,
+                        force_k, mask_bits, kv_idx, kv_cnt, idx_stride, stream);
 }
 
 }  // namespace bsga

@@ -1,0 +1,83 @@
+"""GPU parity at the benchmark's full sizes (configs 3, 4, 5), in the launch configuration
+bench.py times: masks of whole heads bit-exact against the oracle, attention outputs checked on
+sampled (head, query block) units the oracle computes one by one, always including block 0, the
+ragged last block and the rows with the fewest and the most kept blocks."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import bsga_oracle as O
+from workload import CONFIGS, generate
+from tests.helpers import attn_errors, bits_to_mask, oracle_mask_pipeline, to_device, unexcused_mask_mismatches
+
+pytestmark = pytest.mark.gpu
+
+BF16_MAX, BF16_MEAN = 1e-2, 1e-3
+
+
+@pytest.fixture(scope="module")
+def B():
+    import paper_2509_07120_amd as pkg
+    assert torch.cuda.is_available()
+    return pkg
+
+
+def _sample_blocks(kept_counts, nb, rng):
+    picks = {0, nb - 1, int(np.argmin(kept_counts)), int(np.argmax(kept_counts))}
+    picks.update(int(x) for x in rng.integers(0, nb, 2))
+    return sorted(picks)
+
+
+@pytest.mark.parametrize("cfg_id,tau,mask_heads,attn_heads", [(3, 0.9, 16, 2), (4, 0.9, 4, 2), (4, 0.8, 2, 1),
+                                                             (5, 0.9, 2, 1)])
+def test_full_size_layer(B, cfg_id, tau, mask_heads, attn_heads):
+    cfg = CONFIGS[cfg_id]
+    q, k, v = generate(cfg)
+    tq, tk, tv = (to_device(x, cfg.dtype) for x in (q, k, v))
+    out, kv_idx, kv_cnt, bits = B.sparse_global_attention(tq, tk, tv, cfg.block, tau)
+    dense = B.bsga_dense_attn(tq, tk, tv)
+    torch.cuda.synchronize()
+    nb = cfg.n_blocks
+    got_mask = bits_to_mask(bits, nb)
+    cnt = kv_cnt.cpu().numpy()
+    assert (cnt == got_mask.sum(-1)).all()
+    assert torch.isfinite(out.float()).all() and torch.isfinite(dense.float()).all()
+
+    # masks: whole heads against the oracle
+    hs = list(range(mask_heads))
+    _, _, logits, probs, want_mask = oracle_mask_pipeline(q[hs], k[hs], cfg.block, tau, 1.0)
+    unexcused, excused = unexcused_mask_mismatches(got_mask[hs], want_mask, logits, probs, tau, 1.0)
+    assert unexcused == 0, (unexcused, excused)
+    del logits, probs
+
+    # attention: sampled units, sparse against the oracle on the GPU's own mask, dense against Eq. (1)
+    rng = np.random.default_rng(cfg_id)
+    worst = [0.0, 0.0, 0.0, 0.0]
+    for h in range(attn_heads):
+        blocks = _sample_blocks(cnt[h], nb, rng)
+        qh, kh_, vh = q[h:h + 1], k[h:h + 1], v[h:h + 1]
+        want = O.sparse_attention(qh, kh_, vh, got_mask[h:h + 1], cfg.block, q_blocks=blocks)
+        mx, mean = attn_errors(out[h:h + 1], want)
+        full = np.ones((1, nb, nb), dtype=bool)
+        want_d = O.sparse_attention(qh, kh_, vh, full, cfg.block, q_blocks=blocks[:3])
+        dmx, dmean = attn_errors(dense[h:h + 1], want_d)
+        worst = [max(worst[0], mx), max(worst[1], mean), max(worst[2], dmx), max(worst[3], dmean)]
+    print(f"cfg{cfg_id} tau={tau}: kept={got_mask.mean():.4f} mask excused={excused} "
+          f"sparse max/mean={worst[0]:.2e}/{worst[1]:.2e} dense max/mean={worst[2]:.2e}/{worst[3]:.2e}")
+    assert worst[0] <= BF16_MAX and worst[1] <= BF16_MEAN, worst
+    assert worst[2] <= BF16_MAX and worst[3] <= BF16_MEAN, worst
+
+
+def test_topk_only_selection_at_full_size(B):
+    """tau = 0 with a top-k floor (the supplementary sweep of the benchmark): exactly floor(nb (1-rho)) blocks per row."""
+    cfg = CONFIGS[4]
+    q, k, _ = generate(cfg, heads=2)
+    tq, tk = (to_device(x, cfg.dtype) for x in (q, k))
+    qp, kp = B.bsga_pool_qk(tq, tk, cfg.block)
+    for rho in (0.5, 0.75, 0.9):
+        bits, idx, cnt = B.bsga_select_blocks(qp, kp, 0.0, rho)
+        torch.cuda.synchronize()
+        assert (cnt.cpu().numpy() == O.topk_floor(cfg.n_blocks, rho)).all()
+        _, _, logits, probs, want = oracle_mask_pipeline(q, k, cfg.block, 0.0, rho)
+        unexcused, excused = unexcused_mask_mismatches(bits_to_mask(bits, cfg.n_blocks), want, logits, probs, 0.0, rho)
+        assert unexcused == 0, (rho, unexcused, excused)
