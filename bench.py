@@ -2,7 +2,7 @@
 """Benchmark of the block-sparse global-attention layer on one MI355X.
 
 A step is one pass of the whole hot path over one synthetic batch that is already resident in
-HBM: block pooling of Q and K, block scoring + selection, V repack and block-sparse attention.
+HBM: block pooling of Q and K, block scoring + selection, block-sparse attention.
 The default workload is the headline shape: 100 frames x 1374 tokens = 137,400 tokens, 16 heads,
 head dim 64, bf16, block 128, tau = 0.9.  The dense kernel is timed on the same inputs.
 
@@ -39,6 +39,18 @@ def kept_flops(kv_idx, kv_cnt, n_tokens: int, block: int) -> float:
     rows = torch.full((nb,), block, device=kv_idx.device, dtype=torch.int64)
     rows[-1] = tail
     return float((keys * rows[None, :]).sum().item()) * 4.0 * 64.0
+
+
+def measured_traffic(cfg_id: int):
+    """HBM bytes per launch of the attention kernel, from the committed rocprofv3 --pmc summary
+    (profiles/attention_hbm_traffic.json, written from FETCH_SIZE / WRITE_SIZE runs); None if that
+    workload has not been profiled."""
+    path = os.path.join(ROOT, "profiles", "attention_hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(f"cfg{cfg_id}", {}).get("hbm_bytes_per_launch")
+    except (OSError, ValueError):
+        return None
 
 
 def cpu_baseline(cfg, tau: float, budget_s: float = 20.0):
@@ -99,7 +111,10 @@ def main() -> int:
     ap.add_argument("--dense-steps", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
-    ap.add_argument("--sweep", action="store_true", help="also print per-(tau, rho) rows to stderr")
+    ap.add_argument("--sweep", action="store_true", help="also time the (tau, rho) sweep; rows go to stderr and into the JSON")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run one 1 GiB device-to-device copy first (reference dispatch for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding or collectives are implemented); "
@@ -121,8 +136,15 @@ def main() -> int:
     print(f"[bench] generated cfg {cfg.cfg_id} ({cfg.name}) in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
     H, N, d = tq.shape
     b = cfg.block
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     ws_bytes = B.bsga_attn_workspace_bytes(dt, H, N, d)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+    sel_ws = torch.empty(B.bsga_select_workspace_bytes(H, cfg.n_blocks, cfg.n_blocks), dtype=torch.uint8, device="cuda")
     out = torch.empty_like(tq)
 
     def layer(tau, rho, events=None):
@@ -131,7 +153,7 @@ def main() -> int:
         qp, kp = B.bsga_pool_qk(tq, tk, b)
         if events:
             events[1].record()
-        bits, idx, cnt = B.bsga_select_blocks(qp, kp, tau, rho, want_bits=False)
+        bits, idx, cnt = B.bsga_select_blocks(qp, kp, tau, rho, want_bits=False, workspace=sel_ws)
         if events:
             events[2].record()
         B.bsga_sparse_attn(tq, tk, tv, b, idx, cnt, out=out, workspace=ws)
@@ -170,12 +192,16 @@ def main() -> int:
         dense_ms = e0.elapsed_time(e1) / args.dense_steps
     dense_flops = 4.0 * H * float(N) * float(N) * d
 
+    sweep_rows = []
     if args.sweep:
         for tau, rho in [(0.8, 1.0), (0.9, 1.0), (0.95, 1.0), (0.0, 0.5), (0.0, 0.75), (0.0, 0.9)]:
             w, st, fl, kf = run(tau, rho, max(2, args.steps // 2), 1)
-            print(f"[sweep] tau={tau} rho={rho} kept={kf:.4f} layer_ms={w:.3f} pool={st[0]:.3f} select={st[1]:.3f} "
-                  f"attn={st[2]:.3f} kept_TFLOPs={fl / (w * 1e-3) / 1e12:.1f} "
-                  f"speedup_vs_dense={(dense_ms / w) if dense_ms else float('nan'):.3f}", file=sys.stderr, flush=True)
+            row = {"tau": tau, "rho": rho, "kept_fraction": kf, "layer_ms": w, "pool_ms": st[0], "select_ms": st[1],
+                   "attention_ms": st[2], "kept_tflops_layer": fl / (w * 1e-3) / 1e12,
+                   "kept_tflops_attention": fl / (st[2] * 1e-3) / 1e12,
+                   "speedup_vs_dense": (dense_ms / w) if dense_ms else None}
+            sweep_rows.append(row)
+            print("[sweep] " + json.dumps(row), file=sys.stderr, flush=True)
 
     attn_ms = stage[2]
     achieved = flops / (attn_ms * 1e-3) / 1e12
@@ -196,16 +222,20 @@ def main() -> int:
         "config": {"workload": f"cfg{cfg.cfg_id}: {cfg.frames} frames x {cfg.tokens_per_frame} tokens = {N} tokens, "
                                f"{H} heads, d={d}, {cfg.dtype}, block {b}, tau={args.tau}, rho={args.rho}"},
         "layer_ms": wall_ms,
-        "stage_ms": {"pool": stage[0], "select": stage[1], "attention_incl_v_repack": stage[2]},
+        "stage_ms": {"pool": stage[0], "select": stage[1], "attention": stage[2]},
+        "pool_gbs": (2.0 * H * N * d * (2 if cfg.dtype == "bf16" else 4)) / (stage[0] * 1e-3) / 1e9,
         "kept_fraction": kept_frac,
         "pct_of_bf16_peak": 100.0 * value / PEAK_BF16_TFLOPS,
         "dense_ms": dense_ms,
         "dense_tflops": (dense_flops / (dense_ms * 1e-3) / 1e12) if dense_ms else None,
         "speedup_vs_dense": (dense_ms / wall_ms) if dense_ms else None,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
-                     "kernel": "attn_bf16_kernel<128> (block-sparse attention incl. V repack)"},
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(cfg.cfg_id),
+                     "kernel": f"attn_bf16_kernel<{b}> (block-sparse attention, one launch per step)",
+                     "flops_per_launch": flops, "launch_ms": attn_ms},
     }
+    if sweep_rows:
+        rec["sweep"] = sweep_rows
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(cfg, args.tau, args.cpu_budget)
     print(json.dumps(rec), flush=True)

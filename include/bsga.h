@@ -61,6 +61,12 @@ int bsga_pool_qk(const void* q, const void* k, int dtype, int heads, int64_t n_t
                  int block, double* q_pool, double* k_pool, void* stream);
 
 /*
+ * Bytes of device workspace bsga_select_blocks needs: the float64 block logits
+ * [heads, nb_q, nb_k] (Sec. 4.1, the low-resolution score matrix S).  0 for invalid arguments.
+ */
+size_t bsga_select_workspace_bytes(int heads, int nb_q, int nb_k);
+
+/*
  * Block scores, block softmax and block selection  (Sec. 4.1, "Predicting Block Masks" and
  * "Selecting Blocks").  For every head h and query block I:
  *   logits[J] = score_scale * <q_pool[h,I], k_pool[h,J]>,  p = softmax_J(logits)      (float64)
@@ -78,12 +84,16 @@ int bsga_pool_qk(const void* q, const void* k, int dtype, int heads, int64_t n_t
  *   kv_idx    [heads, nb_q, idx_stride] int32, the kept J in ascending order; entries past the
  *             count are left untouched;  idx_stride >= nb_k;
  *   kv_cnt    [heads, nb_q] int32, number of kept blocks.
+ *   workspace, workspace_bytes: device scratch of at least bsga_select_workspace_bytes(...) bytes,
+ *             16-byte aligned; holds the block logits between the two kernels of this call and is
+ *             overwritten; calls sharing one workspace must be stream-ordered.
  * Limits: 1 <= nb_k <= 4096.  score_scale must be finite; 0 <= tau; 0 <= rho <= 1.
  */
 int bsga_select_blocks(const double* q_pool, const double* k_pool, int heads, int nb_q, int nb_k,
                        int head_dim, double score_scale, double tau, double rho,
                        const uint8_t* force_q, const uint8_t* force_k, uint32_t* mask_bits,
-                       int32_t* kv_idx, int32_t* kv_cnt, int idx_stride, void* stream);
+                       int32_t* kv_idx, int32_t* kv_cnt, int idx_stride, void* workspace,
+                       size_t workspace_bytes, void* stream);
 
 /*
  * Bytes of device workspace bsga_sparse_attn / bsga_dense_attn need for this shape.  The current

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     bsga_dense_attn,
     bsga_pool_qk,
     bsga_select_blocks,
+    bsga_select_workspace_bytes,
     bsga_sparse_attn,
     lib,
     num_blocks,

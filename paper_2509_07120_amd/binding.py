@@ -31,6 +31,7 @@ EXPORTED_SYMBOLS = (
     "bsga_version",
     "bsga_last_error",
     "bsga_pool_qk",
+    "bsga_select_workspace_bytes",
     "bsga_select_blocks",
     "bsga_attn_workspace_bytes",
     "bsga_sparse_attn",
@@ -61,7 +62,10 @@ def _load() -> ctypes.CDLL:
     lib.bsga_pool_qk.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int64, c_int, c_int, c_void_p, c_void_p, c_void_p]
     lib.bsga_select_blocks.restype = c_int
     lib.bsga_select_blocks.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_double, c_double, c_double,
-                                       c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p]
+                                       c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_size_t,
+                                       c_void_p]
+    lib.bsga_select_workspace_bytes.restype = c_size_t
+    lib.bsga_select_workspace_bytes.argtypes = [c_int, c_int, c_int]
     lib.bsga_attn_workspace_bytes.restype = c_size_t
     lib.bsga_attn_workspace_bytes.argtypes = [c_int, c_int, c_int64, c_int]
     lib.bsga_sparse_attn.restype = c_int
@@ -125,8 +129,10 @@ def bsga_pool_qk(q: torch.Tensor, k: torch.Tensor, block: int) -> Tuple[torch.Te
 
 def bsga_select_blocks(q_pool: torch.Tensor, k_pool: torch.Tensor, tau: float, rho: float = 1.0,
                        score_scale: Optional[float] = None, force_q: Optional[torch.Tensor] = None,
-                       force_k: Optional[torch.Tensor] = None, want_bits: bool = True):
-    """Pooled Q/K -> (mask_bits [H,nbq,ceil(nbk/32)] uint32-as-int32, kv_idx [H,nbq,nbk] int32, kv_cnt [H,nbq] int32)."""
+                       force_k: Optional[torch.Tensor] = None, want_bits: bool = True,
+                       workspace: Optional[torch.Tensor] = None):
+    """Pooled Q/K -> (mask_bits [H,nbq,ceil(nbk/32)] uint32-as-int32, kv_idx [H,nbq,nbk] int32, kv_cnt [H,nbq] int32).
+    `workspace`: optional device byte buffer of bsga_select_workspace_bytes(H, nbq, nbk) bytes (allocated if absent)."""
     _require(q_pool, "q_pool", torch.float64); _require(k_pool, "k_pool", torch.float64)
     H, nbq, d = q_pool.shape
     nbk = k_pool.shape[1]
@@ -141,10 +147,17 @@ def bsga_select_blocks(q_pool: torch.Tensor, k_pool: torch.Tensor, tau: float, r
         _require(force_q, "force_q", torch.uint8)
     if force_k is not None:
         _require(force_k, "force_k", torch.uint8)
+    if workspace is None:
+        workspace = torch.empty(bsga_select_workspace_bytes(H, nbq, nbk), dtype=torch.uint8, device=dev)
+    ws_bytes = workspace.numel() * workspace.element_size()
     _check(lib.bsga_select_blocks(_ptr(q_pool), _ptr(k_pool), H, nbq, nbk, d, float(score_scale), float(tau),
                                   float(rho), _ptr(force_q), _ptr(force_k), _ptr(mask_bits), _ptr(kv_idx),
-                                  _ptr(kv_cnt), nbk, _stream(q_pool)))
+                                  _ptr(kv_cnt), nbk, _ptr(workspace), ws_bytes, _stream(q_pool)))
     return mask_bits, kv_idx, kv_cnt
+
+
+def bsga_select_workspace_bytes(heads: int, nb_q: int, nb_k: int) -> int:
+    return int(lib.bsga_select_workspace_bytes(heads, nb_q, nb_k))
 
 
 def bsga_attn_workspace_bytes(dtype: torch.dtype, heads: int, n_tokens: int, head_dim: int = 64) -> int:

@@ -92,7 +92,7 @@ using namespace bsga;
 
 extern "C" {
 
-int bsga_version(void) { return 1; }
+int bsga_version(void) { return 2; }
 
 const char* bsga_last_error(void) { return g_err; }
 
@@ -115,9 +115,15 @@ int bsga_pool_qk(const void* q, const void* k, int dtype, int heads, int64_t n_t
   return BSGA_OK;
 }
 
+size_t bsga_select_workspace_bytes(int heads, int nb_q, int nb_k) {
+  if (heads < 1 || nb_q < 1 || nb_k < 1) return 0;
+  return select_workspace_bytes(heads, nb_q, nb_k);
+}
+
 int bsga_select_blocks(const double* q_pool, const double* k_pool, int heads, int nb_q, int nb_k, int head_dim,
                        double score_scale, double tau, double rho, const uint8_t* force_q, const uint8_t* force_k,
-                       uint32_t* mask_bits, int32_t* kv_idx, int32_t* kv_cnt, int idx_stride, void* stream) {
+                       uint32_t* mask_bits, int32_t* kv_idx, int32_t* kv_cnt, int idx_stride, void* workspace,
+                       size_t workspace_bytes, void* stream) {
   const char* fn = "bsga_select_blocks";
   clear_error();
   if (!q_pool || !k_pool) return fail(BSGA_ERR_INVALID_ARG, "%s: q_pool and k_pool must be non-null", fn);
@@ -134,10 +140,15 @@ int bsga_select_blocks(const double* q_pool, const double* k_pool, int heads, in
   if (kv_idx && idx_stride < nb_k)
     return fail(BSGA_ERR_INVALID_ARG, "%s: idx_stride (%d) must be >= nb_k (%d)", fn, idx_stride, nb_k);
   if (!mask_bits && !kv_idx && !kv_cnt) return fail(BSGA_ERR_INVALID_ARG, "%s: no output requested", fn);
+  const size_t need = select_workspace_bytes(heads, nb_q, nb_k);
+  if (!workspace) return fail(BSGA_ERR_WORKSPACE, "%s: workspace is null, %zu bytes needed", fn, need);
+  if (workspace_bytes < need)
+    return fail(BSGA_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", fn, workspace_bytes, need);
+  if (!aligned16(workspace)) return fail(BSGA_ERR_INVALID_ARG, "%s: workspace must be 16-byte aligned", fn);
   // k = floor(B (1 - rho)) in binary64, as the definition is written.
   const int k_floor = static_cast<int>(floor(static_cast<double>(nb_k) * (1.0 - rho)));
   return launch_select(q_pool, k_pool, heads, nb_q, nb_k, score_scale, tau, k_floor, force_q, force_k, mask_bits,
-                       kv_idx, kv_cnt, idx_stride, static_cast<hipStream_t>(stream));
+                       kv_idx, kv_cnt, idx_stride, workspace, static_cast<hipStream_t>(stream));
 }
 
 size_t bsga_attn_workspace_bytes(int dtype, int heads, int64_t n_tokens, int head_dim) {

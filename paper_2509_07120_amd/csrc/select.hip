@@ -1,17 +1,24 @@
 // Block scores, block softmax and block selection (Sec. 4.1, "Predicting Block Masks" and
-// "Selecting Blocks"), all in float64.
+// "Selecting Blocks"), all in float64.  Two kernels:
 //
-// One workgroup of 256 threads handles R consecutive query-block rows of one head:
-//   1. logits[r][J] = scale * <q_pool[I+r], k_pool[J]>  four lanes share one J (16 dims each); every
-//      k_pool element is loaded once and used for all R rows (k_pool of a head is re-read by every
-//      workgroup from L2, which is what bounds this kernel, hence R rows per workgroup)
-// then, row by row:
-//   2. p = softmax(logits)                          block-wide max and sum
-//   3. rank: bitonic sort in LDS by (p descending, J ascending)
-//   4. inclusive scan of p in rank order; n_cdf = 1 + first rank whose running sum reaches tau
-//   5. keep the first n = min(nb_k, max(n_cdf, k, 1)) ranks, OR the forced rows/columns in
-//   6. emit bit mask words, the ascending index list and the count
-// Nothing but the outputs goes to HBM.
+// logits_kernel: one workgroup computes R consecutive query-block rows of one head,
+//     logits[I][J] = scale * <q_pool[I], k_pool[J]>,
+//   four lanes sharing one J (16 dims each).  Every k_pool element is loaded once per workgroup and
+//   used for all R rows: k_pool of a head is re-read by every workgroup from L2, and that traffic is
+//   what bounds this step.  The logits go to a caller-provided workspace [heads, nb_q, nb_k].
+//
+// select_kernel: one WAVE per row, the whole row in registers (lane l holds blocks l, l+64, ...),
+//   no LDS and no barriers.  The ranked prefix the method keeps is found without sorting:
+//   with key(p) = the bit pattern of p (monotone for p >= 0) and, for a threshold key C,
+//       M(C) = sum of p over {key >= C},   cnt(C) = number of blocks with key >= C,
+//   the block at which the ranked cumulative mass first reaches tau is the one with key
+//       T = max{C : cnt(C) >= 1 and M(C) >= tau},
+//   found by bisection over the key range [key(p_min), key(p_max)] (each step one wave-wide sum);
+//   the bisection stops as soon as one block is left in the window.  Blocks above T are kept;
+//   blocks that tie with T are kept in ascending block order while the running mass is below tau.
+//   The top-k floor is the same search with the predicate cnt(C) >= k.  The sums are taken in a
+//   fixed order (lane-local in ascending block order, then a butterfly), so results are
+//   deterministic; adding non-negative terms in a fixed order is monotone, which the bisection needs.
 #include "bsga_internal.h"
 
 namespace bsga {
@@ -21,50 +28,19 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 constexpr int kD = 64;
 
-__device__ inline double wave_max(double v) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) v = fmax(v, __shfl_xor(v, o));
-  return v;
-}
-__device__ inline double wave_sum(double v) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
-  return v;
-}
-
-// rank order: larger p first, equal p by smaller block index
-__device__ inline bool ranks_before(double pa, int ia, double pb, int ib) {
-  return pa > pb || (pa == pb && ia < ib);
-}
-
 template <int R>
-__global__ __launch_bounds__(kThreads) void select_kernel(
-    const double* __restrict__ q_pool, const double* __restrict__ k_pool, int nb_q, int nb_k, int nbp,
-    double score_scale, double tau, int k_floor, const uint8_t* __restrict__ force_q,
-    const uint8_t* __restrict__ force_k, uint32_t* __restrict__ mask_bits, int32_t* __restrict__ kv_idx,
-    int32_t* __restrict__ kv_cnt, int idx_stride) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  double* val = reinterpret_cast<double*>(smem);                 // [nbp] p of the current row -> sorted p
-  int* idx = reinterpret_cast<int*>(smem + size_t(nbp) * 8);     // [nbp] block index per rank
-  double* logit = reinterpret_cast<double*>(smem + size_t(nbp) * 12);  // [R][nb_k] logits of all rows
-  __shared__ double red[kWaves];
-  __shared__ double red2[kWaves];
-  __shared__ int wave_cnt[kWaves];
-  __shared__ int first_rank;
-
+__global__ __launch_bounds__(kThreads) void logits_kernel(const double* __restrict__ q_pool,
+                                                          const double* __restrict__ k_pool, int nb_q, int nb_k,
+                                                          double score_scale, double* __restrict__ logits) {
   const int I0 = blockIdx.x * R;
   const int h = blockIdx.y;
   const int t = threadIdx.x;
-  const int lane = t & 63;
-  const int wave = t >> 6;
-
-  // ---- 1. logits of R rows ----------------------------------------------------------------------
   // lane quarter qd of a group of four handles the 16-byte chunks qd, qd+4, ..., qd+28 of a row
   const int qd = t & 3;
   double2 qv[R][8];
 #pragma unroll
   for (int r = 0; r < R; ++r) {
-    const int I = min(I0 + r, nb_q - 1);  // rows past the end repeat the last row and are not emitted
+    const int I = min(I0 + r, nb_q - 1);  // rows past the end repeat the last row and are not stored
     const double2* qrow = reinterpret_cast<const double2*>(q_pool + (int64_t(h) * nb_q + I) * kD);
 #pragma unroll
     for (int i = 0; i < 8; ++i) qv[r][i] = qrow[4 * i + qd];
@@ -89,161 +65,228 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     for (int r = 0; r < R; ++r) {
       acc[r] += __shfl_xor(acc[r], 1);
       acc[r] += __shfl_xor(acc[r], 2);
-      if (qd == 0 && J < nb_k) logit[r * nb_k + J] = score_scale * acc[r];
+      if (qd == 0 && J < nb_k && I0 + r < nb_q)
+        logits[(int64_t(h) * nb_q + I0 + r) * nb_k + J] = score_scale * acc[r];
     }
-  }
-  __syncthreads();
-
-  for (int rr = 0; rr < R; ++rr) {
-  const int I = I0 + rr;
-  if (I >= nb_q) break;  // uniform
-  const double* lrow = logit + rr * nb_k;
-  // ---- 2. softmax -------------------------------------------------------------------------
-  double m = -INFINITY;
-  for (int J = t; J < nb_k; J += kThreads) m = fmax(m, lrow[J]);
-  m = wave_max(m);
-  if (lane == 0) red[wave] = m;
-  __syncthreads();
-  m = fmax(fmax(red[0], red[1]), fmax(red[2], red[3]));
-  double z = 0.0;
-  for (int J = t; J < nb_k; J += kThreads) {
-    const double e = exp(lrow[J] - m);
-    val[J] = e;
-    z += e;
-  }
-  z = wave_sum(z);
-  if (lane == 0) red2[wave] = z;
-  __syncthreads();
-  z = (red2[0] + red2[1]) + (red2[2] + red2[3]);
-  for (int J = t; J < nbp; J += kThreads) {
-    val[J] = (J < nb_k) ? val[J] / z : -1.0;  // padding ranks after every real block
-    idx[J] = J;
-  }
-  if (t == 0) first_rank = nbp;
-  __syncthreads();
-
-  // ---- 3. bitonic sort into rank order ---------------------------------------------------
-  for (int k = 2; k <= nbp; k <<= 1) {
-    for (int j = k >> 1; j >= 1; j >>= 1) {
-      for (int i = t; i < (nbp >> 1); i += kThreads) {
-        const int a = ((i / j) * (j << 1)) + (i % j);
-        const int b = a + j;
-        const double pa = val[a], pb = val[b];
-        const int ia = idx[a], ib = idx[b];
-        const bool up = (a & k) == 0;  // this sub-sequence must end in rank order
-        const bool swap = up ? ranks_before(pb, ib, pa, ia) : ranks_before(pa, ia, pb, ib);
-        if (swap) {
-          val[a] = pb; val[b] = pa;
-          idx[a] = ib; idx[b] = ia;
-        }
-      }
-      __syncthreads();
-    }
-  }
-
-  // ---- 4. cumulative mass in rank order ---------------------------------------------------
-  const int seg = nbp / kThreads;  // nbp is a multiple of 256
-  const int r0 = t * seg;
-  double local = 0.0;
-  for (int r = r0; r < r0 + seg; ++r) local += (r < nb_k) ? val[r] : 0.0;
-  // exclusive scan of the 256 per-thread totals
-  double incl = local;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const double up = __shfl_up(incl, o);
-    if (lane >= o) incl += up;
-  }
-  if (lane == 63) red[wave] = incl;
-  __syncthreads();
-  double offset = incl - local;
-  for (int w = 0; w < wave; ++w) offset += red[w];
-  if (tau < 1.0) {
-    double run = offset;
-    for (int r = r0; r < r0 + seg && r < nb_k; ++r) {
-      run += val[r];
-      if (run >= tau) {
-        atomicMin(&first_rank, r);
-        break;
-      }
-    }
-  }
-  __syncthreads();
-  const int n_cdf = (first_rank < nb_k) ? first_rank + 1 : nb_k;
-  const int n_keep = min(nb_k, max(max(n_cdf, k_floor), 1));
-  const bool whole_row = force_q != nullptr && force_q[I] != 0;
-  __syncthreads();
-
-  // ---- 5. keep flags (val is reused as the flag array; ranks are read from idx) ------------
-  unsigned char* keep = reinterpret_cast<unsigned char*>(val);
-  for (int J = t; J < nbp; J += kThreads) keep[J] = 0;
-  __syncthreads();
-  for (int r = t; r < n_keep; r += kThreads) keep[idx[r]] = 1;
-  __syncthreads();
-
-  // ---- 6. emit -----------------------------------------------------------------------------
-  const int words = (nb_k + 31) >> 5;
-  const int64_t row = int64_t(h) * nb_q + I;
-  int running = 0;
-  for (int j0 = 0; j0 < nb_k; j0 += kThreads) {
-    const int J = j0 + t;
-    bool f = false;
-    if (J < nb_k) f = whole_row || keep[J] != 0 || (force_k != nullptr && force_k[J] != 0);
-    const unsigned long long bal = __ballot(f);
-    if (lane == 0) {
-      wave_cnt[wave] = __popcll(bal);
-      if (mask_bits != nullptr) {
-        const int w0 = (j0 >> 5) + 2 * wave;
-        if (w0 < words) mask_bits[row * words + w0] = static_cast<uint32_t>(bal);
-        if (w0 + 1 < words) mask_bits[row * words + w0 + 1] = static_cast<uint32_t>(bal >> 32);
-      }
-    }
-    __syncthreads();
-    int pos = running;
-    for (int w = 0; w < wave; ++w) pos += wave_cnt[w];
-    pos += __popcll(bal & ((1ull << lane) - 1ull));
-    if (f && kv_idx != nullptr) kv_idx[row * idx_stride + pos] = J;
-    running += wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
-    __syncthreads();
-  }
-  if (t == 0 && kv_cnt != nullptr) kv_cnt[row] = running;
-  __syncthreads();  // val / idx / first_rank are reused by the next row
   }
 }
 
-template <int R>
-static int launch_rows(const double* q_pool, const double* k_pool, int heads, int nb_q, int nb_k, int nbp,
-                       size_t smem, double score_scale, double tau, int k_floor, const uint8_t* force_q,
-                       const uint8_t* force_k, uint32_t* mask_bits, int32_t* kv_idx, int32_t* kv_cnt, int idx_stride,
-                       hipStream_t stream) {
-  if (smem > 64 * 1024) {
-    if (int rc = check_hip(hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<R>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(smem)),
-                           "bsga_select_blocks: raising the dynamic LDS limit"))
-      return rc;
+__device__ inline double wave_sum_all(double v) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) v += __shfl_xor(v, o);
+  return v;  // the butterfly leaves the same bits in every lane
+}
+__device__ inline int wave_sum_all(int v) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) v += __shfl_xor(v, o);
+  return v;
+}
+__device__ inline uint64_t uniform64(uint64_t v) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v >> 32));
+  return (uint64_t(hi) << 32) | lo;
+}
+
+// Threshold search.  MASS: largest C with cnt(C) >= 1 and M(C) >= tau; otherwise largest C with
+// cnt(C) >= k_target.  Requires the predicate to hold at key_min.  Returns the threshold key T and
+// n_gt = cnt(T+1), mass_gt = M(T+1), ties = number of blocks whose key equals T.
+template <int E, bool MASS>
+__device__ inline uint64_t find_threshold(const double (&p)[E], uint64_t key_min, uint64_t key_max, int nb_k,
+                                          double tau, int k_target, int& n_gt, double& mass_gt, int& ties) {
+  uint64_t lo = key_min, hi = key_max + 1;
+  int cnt_lo = nb_k, cnt_hi = 0;
+  double mass_hi = 0.0;
+  while (cnt_lo - cnt_hi > 1 && hi - lo > 1) {
+    const uint64_t mid = lo + ((hi - lo) >> 1);
+    double s = 0.0;
+    int c = 0;
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+      const bool ge = static_cast<uint64_t>(__double_as_longlong(p[r])) >= mid;  // padding has key 0 < mid
+      s += ge ? p[r] : 0.0;
+      c += ge ? 1 : 0;
+    }
+    c = __builtin_amdgcn_readfirstlane(wave_sum_all(c));
+    const double m = wave_sum_all(s);
+    const bool holds = MASS ? (c >= 1 && m >= tau) : (c >= k_target);
+    if (__builtin_amdgcn_readfirstlane(holds ? 1 : 0)) {
+      lo = mid;
+      cnt_lo = c;
+    } else {
+      hi = mid;
+      cnt_hi = c;
+      mass_hi = m;
+    }
   }
-  dim3 grid((nb_q + R - 1) / R, heads), blk(kThreads);
-  hipLaunchKernelGGL(select_kernel<R>, grid, blk, smem, stream, q_pool, k_pool, nb_q, nb_k, nbp, score_scale, tau,
-                     k_floor, force_q, force_k, mask_bits, kv_idx, kv_cnt, idx_stride);
-  return check_hip(hipGetLastError(), "bsga_select_blocks launch");
+  uint64_t T = lo;
+  if (hi - lo > 1) {  // one block left in [lo, hi): its key is the threshold
+    uint64_t best = 0;
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+      const uint64_t key = static_cast<uint64_t>(__double_as_longlong(p[r]));
+      if (key >= lo && key < hi) best = key;
+    }
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint64_t other = static_cast<uint64_t>(__shfl_xor(static_cast<long long>(best), o));
+      best = best > other ? best : other;
+    }
+    T = uniform64(best);
+  }
+  n_gt = cnt_hi;
+  mass_gt = mass_hi;
+  ties = cnt_lo - cnt_hi;
+  return T;
+}
+
+template <int E>
+__global__ __launch_bounds__(kThreads) void select_kernel(
+    const double* __restrict__ logits, int nb_q, int nb_k, int64_t rows, double tau, int k_floor,
+    const uint8_t* __restrict__ force_q, const uint8_t* __restrict__ force_k, uint32_t* __restrict__ mask_bits,
+    int32_t* __restrict__ kv_idx, int32_t* __restrict__ kv_cnt, int idx_stride) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = int64_t(blockIdx.x) * kWaves + (threadIdx.x >> 6);  // = head * nb_q + I
+  if (row >= rows) return;  // whole wave; the kernel has no barriers
+  const int I = static_cast<int>(row % nb_q);
+  const double* lrow = logits + row * nb_k;
+
+  // ---- softmax: p[r] belongs to block J = 64 r + lane; padding (J >= nb_k) gets p = 0 ----------
+  double p[E];
+  double mx = -INFINITY;
+#pragma unroll
+  for (int r = 0; r < E; ++r) {
+    const int J = r * 64 + lane;
+    p[r] = (J < nb_k) ? lrow[J] : -INFINITY;
+    mx = fmax(mx, p[r]);
+  }
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) mx = fmax(mx, __shfl_xor(mx, o));
+  double z = 0.0;
+#pragma unroll
+  for (int r = 0; r < E; ++r) {
+    p[r] = (r * 64 + lane < nb_k) ? exp(p[r] - mx) : 0.0;
+    z += p[r];
+  }
+  z = wave_sum_all(z);
+  double total = 0.0;
+#pragma unroll
+  for (int r = 0; r < E; ++r) {
+    p[r] = p[r] / z;
+    total += p[r];
+  }
+  total = wave_sum_all(total);
+  // smallest and largest key among the real blocks: the range the bisection works on
+  uint64_t key_min = ~0ull, key_max = 0;
+#pragma unroll
+  for (int r = 0; r < E; ++r) {
+    const uint64_t key = static_cast<uint64_t>(__double_as_longlong(p[r]));
+    if (r * 64 + lane < nb_k) {
+      key_min = key < key_min ? key : key_min;
+      key_max = key > key_max ? key : key_max;
+    }
+  }
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint64_t a = static_cast<uint64_t>(__shfl_xor(static_cast<long long>(key_min), o));
+    const uint64_t b = static_cast<uint64_t>(__shfl_xor(static_cast<long long>(key_max), o));
+    key_min = a < key_min ? a : key_min;
+    key_max = b > key_max ? b : key_max;
+  }
+  key_min = uniform64(key_min);
+  key_max = uniform64(key_max);
+
+  // ---- threshold ----------------------------------------------------------------------------
+  const int k_target = min(nb_k, max(k_floor, 1));
+  bool keep_all = !(total >= tau);  // tau >= 1, or the mass never gets there
+  uint64_t T = 0;
+  int n_ties = 0;
+  if (!keep_all) {
+    int n_gt, ties;
+    double mass_gt;
+    T = find_threshold<E, true>(p, key_min, key_max, nb_k, tau, 0, n_gt, mass_gt, ties);
+    const double pt = __longlong_as_double(static_cast<long long>(T));
+    double run = mass_gt;
+    n_ties = 0;
+    do {
+      run += pt;
+      ++n_ties;
+    } while (run < tau && n_ties < ties);
+    const int n_cdf = n_gt + n_ties;
+    if (n_cdf < k_target) {  // the top-k floor decides
+      T = find_threshold<E, false>(p, key_min, key_max, nb_k, tau, k_target, n_gt, mass_gt, ties);
+      n_ties = k_target - n_gt;
+    }
+  }
+  const bool whole_row = force_q != nullptr && force_q[I] != 0;
+
+  // ---- emit: 64 blocks per step = two mask words; ties are ranked by block index ---------------
+  const int words = (nb_k + 31) >> 5;
+  const unsigned long long below = (1ull << lane) - 1ull;
+  int running = 0, tie_run = 0;
+#pragma unroll
+  for (int r = 0; r < E; ++r) {
+    if (r * 64 < nb_k) {  // uniform
+      const int J = r * 64 + lane;
+      const bool valid = J < nb_k;
+      const uint64_t key = static_cast<uint64_t>(__double_as_longlong(p[r]));
+      const bool tied = valid && key == T;
+      const unsigned long long tb = __ballot(tied);
+      const int tie_idx = tie_run + __popcll(tb & below);
+      bool f = keep_all || whole_row || key > T || (tied && tie_idx < n_ties);
+      if (valid && force_k != nullptr) f = f || force_k[J] != 0;
+      f = f && valid;
+      const unsigned long long bal = __ballot(f);
+      if (mask_bits != nullptr && lane < 2 && 2 * r + lane < words)
+        mask_bits[row * words + 2 * r + lane] = static_cast<uint32_t>(lane == 0 ? bal : (bal >> 32));
+      if (f && kv_idx != nullptr) kv_idx[row * idx_stride + running + __popcll(bal & below)] = J;
+      running += __popcll(bal);
+      tie_run += __popcll(tb);
+    }
+  }
+  if (lane == 0 && kv_cnt != nullptr) kv_cnt[row] = running;
+}
+
+template <int E>
+void launch_select_rows(const double* logits, int heads, int nb_q, int nb_k, double tau, int k_floor,
+                        const uint8_t* force_q, const uint8_t* force_k, uint32_t* mask_bits, int32_t* kv_idx,
+                        int32_t* kv_cnt, int idx_stride, hipStream_t stream) {
+  const int64_t rows = int64_t(heads) * nb_q;
+  hipLaunchKernelGGL(select_kernel<E>, dim3(static_cast<unsigned>((rows + kWaves - 1) / kWaves)), dim3(kThreads), 0,
+                     stream, logits, nb_q, nb_k, rows, tau, k_floor, force_q, force_k, mask_bits, kv_idx, kv_cnt,
+                     idx_stride);
 }
 
 }  // namespace
 
+size_t select_workspace_bytes(int heads, int nb_q, int nb_k) {
+  return size_t(heads) * size_t(nb_q) * size_t(nb_k) * sizeof(double);
+}
+
 int launch_select(const double* q_pool, const double* k_pool, int heads, int nb_q, int nb_k, double score_scale,
                   double tau, int k_floor, const uint8_t* force_q, const uint8_t* force_k, uint32_t* mask_bits,
-                  int32_t* kv_idx, int32_t* kv_cnt, int idx_stride, hipStream_t stream) {
-  int nbp = kThreads;
-  while (nbp < nb_k) nbp <<= 1;
-  // LDS: sort arrays (12 bytes per padded rank) + R rows of logits; up to 96 KB so two workgroups fit a CU
-  auto bytes = [&](int rows) { return size_t(nbp) * 12 + size_t(rows) * nb_k * 8; };
-  if (nb_q >= 4 && bytes(4) <= 96 * 1024)
-    return launch_rows<4>(q_pool, k_pool, heads, nb_q, nb_k, nbp, bytes(4), score_scale, tau, k_floor, force_q,
-                          force_k, mask_bits, kv_idx, kv_cnt, idx_stride, stream);
-  if (nb_q >= 2 && bytes(2) <= 96 * 1024)
-    return launch_rows<2>(q_pool, k_pool, heads, nb_q, nb_k, nbp, bytes(2), score_scale, tau, k_floor, force_q,
-                          force_k, mask_bits, kv_idx, kv_cnt, idx_stride, stream);
-  return launch_rows<1>(q_pool, k_pool, heads, nb_q, nb_k, nbp, bytes(1), score_scale, tau, k_floor, force_q,
-                        force_k, mask_bits, kv_idx, kv_cnt, idx_stride, stream);
+                  int32_t* kv_idx, int32_t* kv_cnt, int idx_stride, void* workspace, hipStream_t stream) {
+  double* logits = static_cast<double*>(workspace);
+  constexpr int R = 4;
+  hipLaunchKernelGGL(logits_kernel<R>, dim3((nb_q + R - 1) / R, heads), dim3(kThreads), 0, stream, q_pool, k_pool,
+                     nb_q, nb_k, score_scale, logits);
+  if (int rc = check_hip(hipGetLastError(), "bsga_select_blocks (logits) launch")) return rc;
+  // per-lane register tile: the smallest instantiation that holds ceil(nb_k / 64) blocks per lane
+  const int e = (nb_k + 63) / 64;
+#define BSGA_SELECT_CASE(E_)                                                                                     \
+  if (e <= E_) {                                                                                                 \
+    launch_select_rows<E_>(logits, heads, nb_q, nb_k, tau, k_floor, force_q, force_k, mask_bits, kv_idx, kv_cnt, \
+                           idx_stride, stream);                                                                  \
+  } else
+  BSGA_SELECT_CASE(4)
+  BSGA_SELECT_CASE(8)
+  BSGA_SELECT_CASE(12)
+  BSGA_SELECT_CASE(20)
+  BSGA_SELECT_CASE(28)
+  BSGA_SELECT_CASE(40)
+  BSGA_SELECT_CASE(52)
+  BSGA_SELECT_CASE(64) { return fail(BSGA_ERR_UNSUPPORTED, "bsga_select_blocks: nb_k = %d exceeds 4096", nb_k); }
+#undef BSGA_SELECT_CASE
+  return check_hip(hipGetLastError(), "bsga_select_blocks launch");
 }
 
 }  // namespace bsga

@@ -28,7 +28,7 @@ def test_header_symbols_are_exported(B):
     raw = ctypes.CDLL(B.LIB_PATH)
     for n in names:
         assert hasattr(raw, n), n
-    assert B.lib.bsga_version() == 1
+    assert B.lib.bsga_version() == 2
 
 
 def test_header_compiles_as_plain_c(tmp_path):
@@ -62,8 +62,10 @@ def test_select_argument_errors(B):
     L = B.lib
     ok = dict(h=16, nbq=10, nbk=10, d=64, s=0.125, tau=0.9, rho=1.0)
 
-    def call(q=A, k=A, h=16, nbq=10, nbk=10, d=64, s=0.125, tau=0.9, rho=1.0, bits=A, idx=A, cnt=A, stride=10):
-        return L.bsga_select_blocks(q, k, h, nbq, nbk, d, s, tau, rho, None, None, bits, idx, cnt, stride, None)
+    def call(q=A, k=A, h=16, nbq=10, nbk=10, d=64, s=0.125, tau=0.9, rho=1.0, bits=A, idx=A, cnt=A, stride=10, ws=A,
+             wsb=1 << 30):
+        return L.bsga_select_blocks(q, k, h, nbq, nbk, d, s, tau, rho, None, None, bits, idx, cnt, stride, ws, wsb,
+                                    None)
 
     assert call(q=None) == 1
     assert call(nbk=0) == 1 and "nb_k" in _err(B)
@@ -75,6 +77,8 @@ def test_select_argument_errors(B):
     assert call(s=float("inf")) == 1
     assert call(stride=9) == 1 and "idx_stride" in _err(B)
     assert call(bits=None, idx=None, cnt=None) == 1 and "no output" in _err(B)
+    assert call(ws=None) == 3 and "workspace" in _err(B)
+    assert call(wsb=16 * 10 * 10 * 8 - 1) == 3 and "12800 needed" in _err(B)
 
 
 def test_attention_argument_errors(B):
@@ -98,5 +102,8 @@ def test_workspace_size(B):
     """The kernels keep every intermediate on chip: no workspace for any shape."""
     import torch
     assert B.bsga_attn_workspace_bytes(torch.bfloat16, 16, 137400) == 0
+    # selection keeps the float64 block logits between its two kernels
+    assert B.bsga_select_workspace_bytes(16, 1074, 1074) == 16 * 1074 * 1074 * 8
+    assert B.bsga_select_workspace_bytes(0, 10, 10) == 0
     assert B.bsga_attn_workspace_bytes(torch.float32, 16, 2748) == 0
     assert B.lib.bsga_attn_workspace_bytes(0, 0, 100, 64) == 0
