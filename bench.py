@@ -123,6 +123,7 @@ def main() -> int:
 
     import torch
     import paper_2509_07120_amd as B
+    from paper_2509_07120_amd.flop_model import attention_only_speedup, theoretical_speedup
     from workload import CONFIGS, generate
 
     cfg = CONFIGS[args.cfg]
@@ -199,7 +200,11 @@ def main() -> int:
             row = {"tau": tau, "rho": rho, "kept_fraction": kf, "layer_ms": w, "pool_ms": st[0], "select_ms": st[1],
                    "attention_ms": st[2], "kept_tflops_layer": fl / (w * 1e-3) / 1e12,
                    "kept_tflops_attention": fl / (st[2] * 1e-3) / 1e12,
-                   "speedup_vs_dense": (dense_ms / w) if dense_ms else None}
+                   "speedup_vs_dense": (dense_ms / w) if dense_ms else None,
+                   # upper bounds from the appendix's FLOP model: the attention kernel alone, and a whole
+                   # VGGT-sized network at this sparsity
+                   "bound_attention_speedup": attention_only_speedup(1.0 - kf),
+                   "bound_end_to_end_speedup": theoretical_speedup(cfg.frames, cfg.tokens_per_frame, 1.0 - kf)}
             sweep_rows.append(row)
             print("[sweep] " + json.dumps(row), file=sys.stderr, flush=True)
 
