@@ -14,6 +14,9 @@ Steps, in the paper's order:
                       k = floor(B (1 - rho)) -> binary block mask M.
   5. sparse_attention Eq. (2): softmax attention restricted to kept blocks.
   6. dense_attention  Eq. (1).
+  7. special_token_attention  Sec. 4.2: the block map is predicted and applied
+                      on patch tokens only; special tokens attend and are
+                      attended densely.
 
 Readings taken where the paper is silent or ambiguous (each is restated at the
 function that uses it):
@@ -34,7 +37,9 @@ function that uses it):
 Pins (tests/test_oracle_*.py): bilinearity of pooled scores, softmax row sums,
 selection minimality/nesting/closed forms, a token-level brute force of the
 masked softmax, keep-all == dense, dense == a library attention routine, a
-closed-form two-key example, and the dropped-mass error bound.
+closed-form two-key example, and the dropped-mass error bound; for Sec. 4.2
+a token-level brute force with an explicit pair mask, special rows == dense
+rows, no special tokens == the plain path, and everything-kept == dense.
 Parity unpinned: the paper's task-accuracy claims (they need datasets and
 trained weights).
 """
@@ -258,3 +263,68 @@ def sparse_global_attention(q, k, v, b: int, tau: float, rho: float,
     """Steps 1-5 chained; returns (O, mask)."""
     mask = predict_mask(q, k, b, tau, rho, score_scale)
     return sparse_attention(q, k, v, mask, b, softmax_scale), mask
+
+
+# --------------------------------------------------------------------------- special tokens (Sec. 4.2)
+def select_blocks_unranked_columns(logits: np.ndarray, tau: float, rho: float,
+                                   dense_k: np.ndarray, dense_q: Optional[np.ndarray] = None) -> np.ndarray:
+    """Block selection when some key blocks take no part in the ranking (Sec. 4.2: the block map
+    is predicted on patch tokens only; everything that touches a special token stays dense).
+
+    Key blocks with dense_k set are removed before the block softmax, so they carry no mass and do
+    not count towards B in k = floor(B (1 - rho)); the rule of Sec. 4.1 runs on the remaining
+    columns; afterwards the removed columns are kept in every row, and query blocks with dense_q
+    set keep every column."""
+    dense_k = np.asarray(dense_k).astype(bool)
+    H, nbq, nbk = logits.shape
+    mask = np.ones((H, nbq, nbk), dtype=bool)
+    ranked = np.flatnonzero(~dense_k)
+    if ranked.size:
+        sub = select_blocks(block_softmax(logits[:, :, ranked]), tau, rho)
+        mask[:, :, ranked] = sub
+    if dense_q is not None:
+        mask[:, np.asarray(dense_q).astype(bool), :] = True
+    return mask
+
+
+def special_token_attention(q, k, v, patch_idx, special_idx, b: int, tau: float, rho: float,
+                            score_scale: Optional[float] = None, softmax_scale: Optional[float] = None,
+                            patch_blocks: Optional[Iterable[int]] = None, heads: Optional[Sequence[int]] = None,
+                            special_rows: bool = True):
+    """Sec. 4.2 as stated: split the tokens into patch tokens X_p (patch_idx, in this order) and
+    special tokens X_s (special_idx).  The block map is predicted from X_p alone (pooling, block
+    scores, selection over blocks of b consecutive entries of patch_idx).  A patch query attends,
+    in ONE softmax, to the patch keys of its kept blocks and to every special key; a special query
+    attends to every token.  Returns (O [H, N, d] in the original token order, patch block mask).
+
+    patch_blocks / heads restrict which patch query blocks are evaluated (others stay NaN);
+    special_rows = False skips the special queries."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    patch_idx = np.asarray(patch_idx, dtype=np.int64)
+    special_idx = np.asarray(special_idx, dtype=np.int64)
+    H, N, d = q.shape
+    assert patch_idx.size + special_idx.size == N
+    assert np.array_equal(np.sort(np.concatenate([patch_idx, special_idx])), np.arange(N))
+    scale = 1.0 / math.sqrt(d) if softmax_scale is None else softmax_scale
+    head_list = list(range(H)) if heads is None else list(heads)
+    qp, kp = q[:, patch_idx], k[:, patch_idx]
+    mask = predict_mask(qp, kp, b, tau, rho, score_scale)
+    n_p = patch_idx.size
+    nbp = num_blocks(n_p, b)
+    out = np.full((H, N, d), np.nan, dtype=np.float64)
+    block_list = list(range(nbp)) if patch_blocks is None else list(patch_blocks)
+    for h in head_list:
+        for I in block_list:
+            rows = patch_idx[I * b: min((I + 1) * b, n_p)]
+            kept = np.flatnonzero(mask[h, I])
+            cols = np.concatenate([patch_idx[J * b: min((J + 1) * b, n_p)] for J in kept] + [special_idx])
+            logits = scale * (q[h, rows] @ k[h, cols].T)
+            e = np.exp(logits - logits.max(axis=1, keepdims=True))
+            out[h, rows] = (e / e.sum(axis=1, keepdims=True)) @ v[h, cols]
+        if special_rows and special_idx.size:
+            logits = scale * (q[h, special_idx] @ k[h].T)
+            e = np.exp(logits - logits.max(axis=1, keepdims=True))
+            out[h, special_idx] = (e / e.sum(axis=1, keepdims=True)) @ v[h]
+    return out, mask
