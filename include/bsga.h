@@ -75,8 +75,12 @@ size_t bsga_select_workspace_bytes(int heads, int nb_q, int nb_k);
  *           (all nb_k blocks if tau >= 1 or the sum never gets there);
  *   k = floor(nb_k * (1 - rho)) evaluated in float64;  n = min(nb_k, max(n_cdf, k, 1));
  *   the first n ranked blocks are kept.
- * Then, if given (Sec. 4.2, special tokens stay dense): force_q[I] != 0 keeps the whole row I,
- * force_k[J] != 0 keeps column J in every row.
+ * Then, if given (Sec. 4.2, everything that touches a special token stays dense):
+ *   force_q[I] != 0 keeps the whole row I;
+ *   force_k[J] == 1 keeps column J in every row (J is still ranked like any other block);
+ *   force_k[J] == 2 keeps column J in every row and takes J OUT of the ranking: it gets no mass in
+ *                   the block softmax and does not count towards B (nb_k above becomes the number
+ *                   of ranked blocks).  This is the patch-only block map of Sec. 4.2.
  *   q_pool   [heads, nb_q, 64] float64      k_pool [heads, nb_k, 64] float64
  *   force_q  nullable [nb_q] uint8          force_k nullable [nb_k] uint8
  * Outputs (each nullable):
@@ -94,6 +98,17 @@ int bsga_select_blocks(const double* q_pool, const double* k_pool, int heads, in
                        const uint8_t* force_q, const uint8_t* force_k, uint32_t* mask_bits,
                        int32_t* kv_idx, int32_t* kv_cnt, int idx_stride, void* workspace,
                        size_t workspace_bytes, void* stream);
+
+/*
+ * Token gather  (Sec. 4.2: the tokens are split into patch tokens X_p and special tokens X_s).
+ *   dst[h, i, :] = src[h, index[i], :]   for i in [0, n_dst)
+ *   src   [heads, n_src, 64], dtype as given      dst [heads, n_dst, 64] same dtype, must not overlap src
+ *   index [n_dst] int32 device array; values outside [0, n_src) are clamped into it
+ * Used to make the patch tokens contiguous (so that no pooled block mixes the two kinds) and to
+ * put the outputs back in the caller's token order (gather with the inverse permutation).
+ */
+int bsga_gather_tokens(const void* src, int dtype, int heads, int64_t n_src, int head_dim,
+                       const int32_t* index, int64_t n_dst, void* dst, void* stream);
 
 /*
  * Bytes of device workspace bsga_sparse_attn / bsga_dense_attn need for this shape.  The current

@@ -33,6 +33,7 @@ EXPORTED_SYMBOLS = (
     "bsga_pool_qk",
     "bsga_select_workspace_bytes",
     "bsga_select_blocks",
+    "bsga_gather_tokens",
     "bsga_attn_workspace_bytes",
     "bsga_sparse_attn",
     "bsga_dense_attn",
@@ -66,6 +67,8 @@ def _load() -> ctypes.CDLL:
                                        c_void_p]
     lib.bsga_select_workspace_bytes.restype = c_size_t
     lib.bsga_select_workspace_bytes.argtypes = [c_int, c_int, c_int]
+    lib.bsga_gather_tokens.restype = c_int
+    lib.bsga_gather_tokens.argtypes = [c_void_p, c_int, c_int, c_int64, c_int, c_void_p, c_int64, c_void_p, c_void_p]
     lib.bsga_attn_workspace_bytes.restype = c_size_t
     lib.bsga_attn_workspace_bytes.argtypes = [c_int, c_int, c_int64, c_int]
     lib.bsga_sparse_attn.restype = c_int
@@ -217,3 +220,54 @@ def sparse_global_attention(q, k, v, block: int, tau: float, rho: float = 1.0,
     mask_bits, kv_idx, kv_cnt = bsga_select_blocks(q_pool, k_pool, tau, rho, score_scale)
     out = bsga_sparse_attn(q, k, v, block, kv_idx, kv_cnt, softmax_scale, workspace=workspace)
     return out, kv_idx, kv_cnt, mask_bits
+
+
+def bsga_gather_tokens(x: torch.Tensor, index: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """out[h, i] = x[h, index[i]] for x [H, N, 64] and an int32 device index [n_out]."""
+    _require(x, "x"); _require(index, "index", torch.int32)
+    H, N, d = x.shape
+    n_out = index.numel()
+    if out is None:
+        out = torch.empty((H, n_out, d), dtype=x.dtype, device=x.device)
+    _check(lib.bsga_gather_tokens(_ptr(x), _dtype_code(x), H, N, d, _ptr(index), n_out, _ptr(out), _stream(x)))
+    return out
+
+
+class SpecialTokenPlan:
+    """Index bookkeeping for the special-token split (Sec. 4.2), built once per sequence layout.
+
+    The working order puts the patch tokens first (in their original order) and the special tokens
+    last.  The first n_patch_blocks = floor(N_p / block) blocks then hold patch tokens only; they are
+    the blocks the map is predicted on.  Every later block (the N_p mod block left-over patch tokens
+    and all special tokens) is attended and attends densely: force_q = 1, force_k = 2 (kept, not
+    ranked)."""
+
+    def __init__(self, special: torch.Tensor, block: int, device):
+        special = torch.as_tensor(special, dtype=torch.bool).cpu()
+        n = special.numel()
+        order = torch.cat([torch.nonzero(~special).flatten(), torch.nonzero(special).flatten()])
+        inverse = torch.empty_like(order)
+        inverse[order] = torch.arange(n)
+        self.n_tokens = n
+        self.block = block
+        self.n_patch = int((~special).sum())
+        self.n_patch_blocks = self.n_patch // block
+        nb = num_blocks(n, block)
+        dense = torch.arange(nb) >= self.n_patch_blocks
+        self.perm = order.to(torch.int32).to(device)
+        self.inverse = inverse.to(torch.int32).to(device)
+        self.force_q = dense.to(torch.uint8).to(device)
+        self.force_k = (dense.to(torch.uint8) * 2).to(device)
+
+
+def sparse_global_attention_special(q, k, v, plan: SpecialTokenPlan, tau: float, rho: float = 1.0,
+                                    score_scale: Optional[float] = None, softmax_scale: Optional[float] = None):
+    """The layer with the special-token split: gather into the working order, pool, select on the
+    patch blocks only, block-sparse attention, gather back.  Returns (O in the caller's token order,
+    kv_idx, kv_cnt, mask_bits); the lists refer to blocks of the working order."""
+    qw, kw, vw = (bsga_gather_tokens(x, plan.perm) for x in (q, k, v))
+    q_pool, k_pool = bsga_pool_qk(qw, kw, plan.block)
+    mask_bits, kv_idx, kv_cnt = bsga_select_blocks(q_pool, k_pool, tau, rho, score_scale, force_q=plan.force_q,
+                                                   force_k=plan.force_k)
+    ow = bsga_sparse_attn(qw, kw, vw, plan.block, kv_idx, kv_cnt, softmax_scale)
+    return bsga_gather_tokens(ow, plan.inverse), kv_idx, kv_cnt, mask_bits

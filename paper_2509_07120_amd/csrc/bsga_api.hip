@@ -145,10 +145,25 @@ int bsga_select_blocks(const double* q_pool, const double* k_pool, int heads, in
   if (workspace_bytes < need)
     return fail(BSGA_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", fn, workspace_bytes, need);
   if (!aligned16(workspace)) return fail(BSGA_ERR_INVALID_ARG, "%s: workspace must be 16-byte aligned", fn);
-  // k = floor(B (1 - rho)) in binary64, as the definition is written.
-  const int k_floor = static_cast<int>(floor(static_cast<double>(nb_k) * (1.0 - rho)));
-  return launch_select(q_pool, k_pool, heads, nb_q, nb_k, score_scale, tau, k_floor, force_q, force_k, mask_bits,
+  return launch_select(q_pool, k_pool, heads, nb_q, nb_k, score_scale, tau, 1.0 - rho, force_q, force_k, mask_bits,
                        kv_idx, kv_cnt, idx_stride, workspace, static_cast<hipStream_t>(stream));
+}
+
+int bsga_gather_tokens(const void* src, int dtype, int heads, int64_t n_src, int head_dim, const int32_t* index,
+                       int64_t n_dst, void* dst, void* stream) {
+  const char* fn = "bsga_gather_tokens";
+  clear_error();
+  if (!src || !dst || !index) return fail(BSGA_ERR_INVALID_ARG, "%s: src, index and dst must be non-null", fn);
+  if (!aligned16(src) || !aligned16(dst)) return fail(BSGA_ERR_INVALID_ARG, "%s: src and dst must be 16-byte aligned", fn);
+  if (dtype != BSGA_BF16 && dtype != BSGA_FP32) return fail(BSGA_ERR_INVALID_ARG, "%s: unknown dtype %d", fn, dtype);
+  if (heads < 1 || heads > 65535) return fail(BSGA_ERR_INVALID_ARG, "%s: heads must be in [1, 65535], got %d", fn, heads);
+  if (head_dim != 64) return fail(BSGA_ERR_UNSUPPORTED, "%s: head_dim must be 64, got %d", fn, head_dim);
+  if (n_src < 1 || n_src > (int64_t(1) << 24))
+    return fail(BSGA_ERR_INVALID_ARG, "%s: n_src must be in [1, 2^24], got %lld", fn, static_cast<long long>(n_src));
+  if (n_dst < 0 || n_dst > (int64_t(1) << 24))
+    return fail(BSGA_ERR_INVALID_ARG, "%s: n_dst must be in [0, 2^24], got %lld", fn, static_cast<long long>(n_dst));
+  if (n_dst == 0) return BSGA_OK;
+  return launch_gather(src, dtype, heads, n_src, index, n_dst, dst, static_cast<hipStream_t>(stream));
 }
 
 size_t bsga_attn_workspace_bytes(int dtype, int heads, int64_t n_tokens, int head_dim) {

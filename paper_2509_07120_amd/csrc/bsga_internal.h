@@ -23,10 +23,13 @@ int launch_pool(const void* x, int dtype, int heads, int64_t n_tokens, int block
                 hipStream_t stream);
 
 int launch_select(const double* q_pool, const double* k_pool, int heads, int nb_q, int nb_k,
-                  double score_scale, double tau, int k_floor, const uint8_t* force_q,
+                  double score_scale, double tau, double one_minus_rho, const uint8_t* force_q,
                   const uint8_t* force_k, uint32_t* mask_bits, int32_t* kv_idx, int32_t* kv_cnt,
                   int idx_stride, void* workspace, hipStream_t stream);
 size_t select_workspace_bytes(int heads, int nb_q, int nb_k);
+
+int launch_gather(const void* src, int dtype, int heads, int64_t n_src, const int32_t* index,
+                  int64_t n_dst, void* dst, hipStream_t stream);
 
 int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int64_t n_tokens,
                      int block, float softmax_scale, const int32_t* kv_idx, const int32_t* kv_cnt,

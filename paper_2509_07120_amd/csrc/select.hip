@@ -141,7 +141,7 @@ __device__ inline uint64_t find_threshold(const double (&p)[E], uint64_t key_min
 
 template <int E>
 __global__ __launch_bounds__(kThreads) void select_kernel(
-    const double* __restrict__ logits, int nb_q, int nb_k, int64_t rows, double tau, int k_floor,
+    const double* __restrict__ logits, int nb_q, int nb_k, int64_t rows, double tau, double one_minus_rho,
     const uint8_t* __restrict__ force_q, const uint8_t* __restrict__ force_k, uint32_t* __restrict__ mask_bits,
     int32_t* __restrict__ kv_idx, int32_t* __restrict__ kv_cnt, int idx_stride) {
   const int lane = threadIdx.x & 63;
@@ -150,37 +150,43 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
   const int I = static_cast<int>(row % nb_q);
   const double* lrow = logits + row * nb_k;
 
-  // ---- softmax: p[r] belongs to block J = 64 r + lane; padding (J >= nb_k) gets p = 0 ----------
+  // ---- softmax over the ranked blocks: p[r] belongs to block J = 64 r + lane.  Padding (J >= nb_k)
+  // and blocks with force_k[J] == 2 (always kept, not ranked) get p = 0 and take no part below.
   double p[E];
+  unsigned long long ranked = 0;  // bit r: block 64 r + lane is ranked
   double mx = -INFINITY;
 #pragma unroll
   for (int r = 0; r < E; ++r) {
     const int J = r * 64 + lane;
-    p[r] = (J < nb_k) ? lrow[J] : -INFINITY;
+    bool rk = J < nb_k;
+    if (rk && force_k != nullptr) rk = force_k[J] != 2;
+    if (rk) ranked |= 1ull << r;
+    p[r] = rk ? lrow[J] : -INFINITY;
     mx = fmax(mx, p[r]);
   }
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) mx = fmax(mx, __shfl_xor(mx, o));
+  const int nb_ranked = __builtin_amdgcn_readfirstlane(wave_sum_all(static_cast<int>(__popcll(ranked))));
   double z = 0.0;
 #pragma unroll
   for (int r = 0; r < E; ++r) {
-    p[r] = (r * 64 + lane < nb_k) ? exp(p[r] - mx) : 0.0;
+    p[r] = ((ranked >> r) & 1) ? exp(p[r] - mx) : 0.0;
     z += p[r];
   }
   z = wave_sum_all(z);
   double total = 0.0;
 #pragma unroll
   for (int r = 0; r < E; ++r) {
-    p[r] = p[r] / z;
+    p[r] = ((ranked >> r) & 1) ? p[r] / z : 0.0;
     total += p[r];
   }
   total = wave_sum_all(total);
-  // smallest and largest key among the real blocks: the range the bisection works on
+  // smallest and largest key among the ranked blocks: the range the bisection works on
   uint64_t key_min = ~0ull, key_max = 0;
 #pragma unroll
   for (int r = 0; r < E; ++r) {
     const uint64_t key = static_cast<uint64_t>(__double_as_longlong(p[r]));
-    if (r * 64 + lane < nb_k) {
+    if ((ranked >> r) & 1) {
       key_min = key < key_min ? key : key_min;
       key_max = key > key_max ? key : key_max;
     }
@@ -196,14 +202,17 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
   key_max = uniform64(key_max);
 
   // ---- threshold ----------------------------------------------------------------------------
-  const int k_target = min(nb_k, max(k_floor, 1));
-  bool keep_all = !(total >= tau);  // tau >= 1, or the mass never gets there
+  // k = floor(B (1 - rho)) in binary64 as the definition is written, B = number of ranked blocks
+  const int k_floor = static_cast<int>(floor(static_cast<double>(nb_ranked) * one_minus_rho));
+  const int k_target = min(nb_ranked, max(k_floor, 1));
+  // tau >= 1, or the mass never gets there (also: nothing is ranked)
+  const bool keep_all = !(total >= tau) || nb_ranked == 0;
   uint64_t T = 0;
   int n_ties = 0;
   if (!keep_all) {
     int n_gt, ties;
     double mass_gt;
-    T = find_threshold<E, true>(p, key_min, key_max, nb_k, tau, 0, n_gt, mass_gt, ties);
+    T = find_threshold<E, true>(p, key_min, key_max, nb_ranked, tau, 0, n_gt, mass_gt, ties);
     const double pt = __longlong_as_double(static_cast<long long>(T));
     double run = mass_gt;
     n_ties = 0;
@@ -213,7 +222,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     } while (run < tau && n_ties < ties);
     const int n_cdf = n_gt + n_ties;
     if (n_cdf < k_target) {  // the top-k floor decides
-      T = find_threshold<E, false>(p, key_min, key_max, nb_k, tau, k_target, n_gt, mass_gt, ties);
+      T = find_threshold<E, false>(p, key_min, key_max, nb_ranked, tau, k_target, n_gt, mass_gt, ties);
       n_ties = k_target - n_gt;
     }
   }
@@ -229,10 +238,12 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
       const int J = r * 64 + lane;
       const bool valid = J < nb_k;
       const uint64_t key = static_cast<uint64_t>(__double_as_longlong(p[r]));
-      const bool tied = valid && key == T;
+      const bool rk = (ranked >> r) & 1;
+      const bool tied = rk && key == T;
       const unsigned long long tb = __ballot(tied);
       const int tie_idx = tie_run + __popcll(tb & below);
-      bool f = keep_all || whole_row || key > T || (tied && tie_idx < n_ties);
+      bool f = rk && (keep_all || key > T || (tied && tie_idx < n_ties));
+      f = f || whole_row;
       if (valid && force_k != nullptr) f = f || force_k[J] != 0;
       f = f && valid;
       const unsigned long long bal = __ballot(f);
@@ -247,12 +258,12 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
 }
 
 template <int E>
-void launch_select_rows(const double* logits, int heads, int nb_q, int nb_k, double tau, int k_floor,
+void launch_select_rows(const double* logits, int heads, int nb_q, int nb_k, double tau, double one_minus_rho,
                         const uint8_t* force_q, const uint8_t* force_k, uint32_t* mask_bits, int32_t* kv_idx,
                         int32_t* kv_cnt, int idx_stride, hipStream_t stream) {
   const int64_t rows = int64_t(heads) * nb_q;
   hipLaunchKernelGGL(select_kernel<E>, dim3(static_cast<unsigned>((rows + kWaves - 1) / kWaves)), dim3(kThreads), 0,
-                     stream, logits, nb_q, nb_k, rows, tau, k_floor, force_q, force_k, mask_bits, kv_idx, kv_cnt,
+                     stream, logits, nb_q, nb_k, rows, tau, one_minus_rho, force_q, force_k, mask_bits, kv_idx, kv_cnt,
                      idx_stride);
 }
 
@@ -263,7 +274,7 @@ size_t select_workspace_bytes(int heads, int nb_q, int nb_k) {
 }
 
 int launch_select(const double* q_pool, const double* k_pool, int heads, int nb_q, int nb_k, double score_scale,
-                  double tau, int k_floor, const uint8_t* force_q, const uint8_t* force_k, uint32_t* mask_bits,
+                  double tau, double one_minus_rho, const uint8_t* force_q, const uint8_t* force_k, uint32_t* mask_bits,
                   int32_t* kv_idx, int32_t* kv_cnt, int idx_stride, void* workspace, hipStream_t stream) {
   double* logits = static_cast<double*>(workspace);
   constexpr int R = 4;
@@ -274,7 +285,7 @@ int launch_select(const double* q_pool, const double* k_pool, int heads, int nb_
   const int e = (nb_k + 63) / 64;
 #define BSGA_SELECT_CASE(E_)                                                                                     \
   if (e <= E_) {                                                                                                 \
-    launch_select_rows<E_>(logits, heads, nb_q, nb_k, tau, k_floor, force_q, force_k, mask_bits, kv_idx, kv_cnt, \
+    launch_select_rows<E_>(logits, heads, nb_q, nb_k, tau, one_minus_rho, force_q, force_k, mask_bits, kv_idx, kv_cnt, \
                            idx_stride, stream);                                                                  \
   } else
   BSGA_SELECT_CASE(4)

@@ -81,6 +81,17 @@ def test_select_argument_errors(B):
     assert call(wsb=16 * 10 * 10 * 8 - 1) == 3 and "12800 needed" in _err(B)
 
 
+def test_gather_argument_errors(B):
+    L = B.lib
+    assert L.bsga_gather_tokens(None, 0, 16, 100, 64, A, 100, A, None) == 1
+    assert L.bsga_gather_tokens(A, 0, 16, 100, 64, None, 100, A, None) == 1 and "index" in _err(B)
+    assert L.bsga_gather_tokens(A, 2, 16, 100, 64, A, 100, A, None) == 1 and "dtype" in _err(B)
+    assert L.bsga_gather_tokens(A, 0, 16, 100, 32, A, 100, A, None) == 2
+    assert L.bsga_gather_tokens(A, 0, 16, 0, 64, A, 100, A, None) == 1 and "n_src" in _err(B)
+    assert L.bsga_gather_tokens(A, 0, 16, 100, 64, A, -1, A, None) == 1 and "n_dst" in _err(B)
+    assert L.bsga_gather_tokens(A, 0, 16, 100, 64, A, 0, A, None) == 0  # nothing to do, nothing launched
+
+
 def test_attention_argument_errors(B):
     L = B.lib
 

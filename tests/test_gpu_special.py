@@ -1,0 +1,143 @@
+"""GPU parity for the special-token split (Sec. 4.2): token gather, selection with unranked key
+blocks, and the whole layer against the oracle's statement of that section."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import bsga_oracle as O
+from workload import CONFIGS, generate
+from tests.helpers import attn_errors, bits_to_mask, lists_to_mask, to_device, unexcused_mask_mismatches
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import paper_2509_07120_amd as pkg
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return pkg
+
+
+def _special_flags(frames, per_frame, n_special=5):
+    return (np.arange(frames * per_frame) % per_frame) < n_special
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_gather_is_exact(B, dtype):
+    rng = np.random.default_rng(0)
+    H, N = 3, 1000
+    x = rng.standard_normal((H, N, 64)).astype(np.float32)
+    tx = to_device(x, dtype)
+    index = rng.integers(0, N, 777).astype(np.int32)
+    got = B.bsga_gather_tokens(tx, torch.from_numpy(index).cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(got, tx[:, torch.from_numpy(index.astype(np.int64)).cuda()])
+    # out-of-range indices are clamped, never read outside the tensor
+    wild = np.array([-5, 0, N - 1, N, 2 ** 30], dtype=np.int32)
+    got = B.bsga_gather_tokens(tx, torch.from_numpy(wild).cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(got, tx[:, torch.tensor([0, 0, N - 1, N - 1, N - 1]).cuda()])
+    # a permutation followed by its inverse is the identity
+    perm = rng.permutation(N).astype(np.int32)
+    inv = np.empty_like(perm)
+    inv[perm] = np.arange(N, dtype=np.int32)
+    back = B.bsga_gather_tokens(B.bsga_gather_tokens(tx, torch.from_numpy(perm).cuda()), torch.from_numpy(inv).cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(back, tx)
+
+
+@pytest.mark.parametrize("nb,tau,rho", [(10, 0.6, 1.0), (130, 0.8, 1.0), (130, 0.0, 0.5), (700, 0.9, 0.9), (64, 1.0, 1.0)])
+def test_select_with_unranked_columns(B, nb, tau, rho):
+    rng = np.random.default_rng(nb)
+    H = 2
+    qp = rng.standard_normal((H, nb, 64)) * 1.5
+    kp = rng.standard_normal((H, nb, 64)) * 1.5
+    fk = np.zeros(nb, np.uint8)
+    fk[rng.choice(nb, max(1, nb // 7), replace=False)] = 2
+    fk[rng.choice(nb, 2, replace=False)] |= 1          # a few "kept but ranked" columns (and 3 = both bits -> != 2)
+    fq = np.zeros(nb, np.uint8)
+    fq[nb // 2] = 1
+    logits = O.block_logits(qp, kp, 0.125)
+    want = O.select_blocks_unranked_columns(logits, tau, rho, fk == 2, fq)
+    want[:, :, fk != 0] = True
+    bits, idx, cnt = B.bsga_select_blocks(torch.from_numpy(qp).cuda(), torch.from_numpy(kp).cuda(), tau, rho,
+                                          force_q=torch.from_numpy(fq).cuda(), force_k=torch.from_numpy(fk).cuda())
+    torch.cuda.synchronize()
+    got = bits_to_mask(bits, nb)
+    assert (lists_to_mask(idx, cnt, nb) == got).all()
+    assert (got == want).all(), int((got != want).sum())
+
+
+def test_all_columns_unranked_keeps_everything(B):
+    rng = np.random.default_rng(1)
+    qp = rng.standard_normal((1, 9, 64))
+    kp = rng.standard_normal((1, 9, 64))
+    fk = np.full(9, 2, np.uint8)
+    bits, idx, cnt = B.bsga_select_blocks(torch.from_numpy(qp).cuda(), torch.from_numpy(kp).cuda(), 0.5, 1.0,
+                                          force_k=torch.from_numpy(fk).cuda())
+    torch.cuda.synchronize()
+    assert bits_to_mask(bits, 9).all() and (cnt.cpu().numpy() == 9).all()
+
+
+def _run_layer(B, cfg, heads, frames, tau, rho, patch_blocks):
+    q, k, v = generate(cfg, heads=heads, frames=frames)
+    N = q.shape[1]
+    special = _special_flags(frames, cfg.tokens_per_frame)
+    b = cfg.block
+    n_patch = int((~special).sum())
+    npb = n_patch // b
+    # the oracle's sets: X_p = the first npb*b patch tokens, X_s = everything else
+    patch_all = np.flatnonzero(~special)
+    patch_idx = patch_all[: npb * b]
+    special_idx = np.sort(np.concatenate([patch_all[npb * b:], np.flatnonzero(special)]))
+    plan = B.SpecialTokenPlan(torch.from_numpy(special), b, "cuda")
+    assert plan.n_patch_blocks == npb
+    tq, tk, tv = (to_device(x, cfg.dtype) for x in (q, k, v))
+    out, idx, cnt, bits = B.sparse_global_attention_special(tq, tk, tv, plan, tau, rho)
+    torch.cuda.synchronize()
+    blocks = list(range(npb)) if patch_blocks is None else [I for I in patch_blocks if I < npb]
+    want, want_mask = O.special_token_attention(q, k, v, patch_idx, special_idx, b, tau, rho, patch_blocks=blocks)
+    # block map: rows/columns of the pure patch blocks against the oracle's patch-only map
+    nb = -(-N // b)
+    mask = bits_to_mask(bits, nb)
+    assert (lists_to_mask(idx, cnt, nb) == mask).all()
+    assert mask[:, npb:, :].all() and mask[:, :, npb:].all(), "special rows and columns must be dense"
+    sub = mask[:, :npb, :npb]
+    qp, kp = O.pool_blocks(q[:, patch_idx], b), O.pool_blocks(k[:, patch_idx], b)
+    logits = O.block_logits(qp, kp, 1.0 / 8.0)
+    unexcused, excused = unexcused_mask_mismatches(sub, want_mask, logits, O.block_softmax(logits), tau, rho)
+    assert unexcused == 0, (unexcused, excused)
+    # outputs: the evaluated patch rows and every special row, in the caller's token order
+    rows = np.concatenate([patch_idx[I * b:(I + 1) * b] for I in blocks] + [special_idx])
+    assert not np.isnan(want[:, rows]).any()
+    mx, mean = attn_errors(out[:, torch.from_numpy(rows).cuda()], want[:, rows])
+    kept = float(sub.mean())
+    print(f"cfg{cfg.cfg_id} frames={frames} tau={tau} rho={rho}: patch kept={kept:.4f} max={mx:.2e} mean={mean:.2e} "
+          f"excused={excused}")
+    return mx, mean, kept
+
+
+def test_layer_config2_shape(B):
+    mx, mean, kept = _run_layer(B, CONFIGS[2], heads=2, frames=8, tau=0.9, rho=1.0, patch_blocks=None)
+    assert mx <= 1e-2 and mean <= 1e-3
+    assert kept < 0.97
+
+
+def test_layer_top_k_only(B):
+    mx, mean, kept = _run_layer(B, CONFIGS[2], heads=2, frames=8, tau=0.0, rho=0.75, patch_blocks=None)
+    assert mx <= 1e-2 and mean <= 1e-3
+    assert abs(kept - 0.25) < 0.01
+
+
+def test_layer_fp32_config1_shape(B):
+    mx, mean, _ = _run_layer(B, CONFIGS[1], heads=2, frames=2, tau=0.9, rho=1.0, patch_blocks=None)
+    assert mx <= 1e-5 and mean <= 1e-6
+
+
+def test_layer_full_size_100_frames_sampled(B):
+    """Headline shape with the split, one head; sampled patch blocks (first, last, a few inside) and
+    all 500 special rows plus the left-over patch rows."""
+    cfg = CONFIGS[4]
+    mx, mean, kept = _run_layer(B, cfg, heads=1, frames=cfg.frames, tau=0.9, rho=1.0,
+                                patch_blocks=[0, 1, 517, 1067, 1068])
+    assert mx <= 1e-2 and mean <= 1e-3
