@@ -112,6 +112,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     ap.add_argument("--sweep", action="store_true", help="also time the (tau, rho) sweep; rows go to stderr and into the JSON")
+    ap.add_argument("--special", action="store_true",
+                    help="also time the layer with the special-token split (gathers included); goes into the JSON")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run one 1 GiB device-to-device copy first (reference dispatch for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -208,6 +210,58 @@ def main() -> int:
             sweep_rows.append(row)
             print("[sweep] " + json.dumps(row), file=sys.stderr, flush=True)
 
+    special_rec = None
+    if args.special:
+        # Sec. 4.2: patch tokens first, special tokens last; block map on the pure patch blocks only
+        import numpy as np
+        flags = torch.from_numpy((np.arange(N) % cfg.tokens_per_frame) < 5)
+        plan = B.SpecialTokenPlan(flags, b, "cuda")
+        gq, gk, gv, go = (torch.empty_like(tq) for _ in range(4))
+        out_sp = torch.empty_like(tq)
+
+        def special_layer(tau, rho, ev=None):
+            if ev:
+                ev[0].record()
+            for src, dst in ((tq, gq), (tk, gk), (tv, gv)):
+                B.bsga_gather_tokens(src, plan.perm, out=dst)
+            if ev:
+                ev[1].record()
+            qp, kp = B.bsga_pool_qk(gq, gk, b)
+            _, idx, cnt = B.bsga_select_blocks(qp, kp, tau, rho, want_bits=False, workspace=sel_ws,
+                                               force_q=plan.force_q, force_k=plan.force_k)
+            if ev:
+                ev[2].record()
+            B.bsga_sparse_attn(gq, gk, gv, b, idx, cnt, out=go, workspace=ws)
+            if ev:
+                ev[3].record()
+            B.bsga_gather_tokens(go, plan.inverse, out=out_sp)
+            if ev:
+                ev[4].record()
+            return idx, cnt
+
+        rows_sp = []
+        for tau, rho in [(args.tau, args.rho), (0.0, 0.5), (0.0, 0.75), (0.0, 0.9)]:
+            special_layer(tau, rho)
+            torch.cuda.synchronize()
+            steps = max(2, args.steps // 2)
+            evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
+            t0 = time.perf_counter()
+            for s_ in range(steps):
+                idx, cnt = special_layer(tau, rho, evs[s_])
+            torch.cuda.synchronize()
+            w = (time.perf_counter() - t0) * 1e3 / steps
+            st = [sum(e[i].elapsed_time(e[i + 1]) for e in evs) / steps for i in range(4)]
+            fl = kept_flops(idx, cnt, N, b)
+            kf = float(cnt.to(torch.float64).sum().item()) / (H * cfg.n_blocks * cfg.n_blocks)
+            row = {"tau": tau, "rho": rho, "kept_fraction": kf, "layer_ms": w, "gather_in_ms": st[0],
+                   "pool_select_ms": st[1], "attention_ms": st[2], "gather_out_ms": st[3],
+                   "gather_gbs": (2.0 * 4 * H * N * d * 2) / ((st[0] + st[3]) * 1e-3) / 1e9,
+                   "kept_tflops_layer": fl / (w * 1e-3) / 1e12,
+                   "speedup_vs_dense": (dense_ms / w) if dense_ms else None}
+            rows_sp.append(row)
+            print("[special] " + json.dumps(row), file=sys.stderr, flush=True)
+        special_rec = {"n_patch_blocks": plan.n_patch_blocks, "n_blocks": cfg.n_blocks, "rows": rows_sp}
+
     attn_ms = stage[2]
     achieved = flops / (attn_ms * 1e-3) / 1e12
     value = flops / (wall_ms * 1e-3) / 1e12
@@ -241,6 +295,8 @@ def main() -> int:
     }
     if sweep_rows:
         rec["sweep"] = sweep_rows
+    if special_rec:
+        rec["special_token_split"] = special_rec
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(cfg, args.tau, args.cpu_budget)
     print(json.dumps(rec), flush=True)

@@ -111,9 +111,10 @@ int bsga_gather_tokens(const void* src, int dtype, int heads, int64_t n_src, int
                        const int32_t* index, int64_t n_dst, void* dst, void* stream);
 
 /*
- * Bytes of device workspace bsga_sparse_attn / bsga_dense_attn need for this shape.  The current
- * kernels read Q, K and V in place and keep all intermediates on chip, so this is 0 for every
- * shape (and for invalid arguments); callers should still query it and pass what it asks for.
+ * Bytes of device workspace bsga_sparse_attn needs for this shape (bsga_dense_attn needs none and
+ * accepts NULL).  Q, K and V are read in place and all intermediates stay on chip; the workspace
+ * holds the launch order of the (head, query block) rows, heaviest first (4 bytes per row, sized for
+ * block 64, plus 128 bytes per head and 16 bytes; 0 for fp32 and for invalid arguments).
  */
 size_t bsga_attn_workspace_bytes(int dtype, int heads, int64_t n_tokens, int head_dim);
 
@@ -126,9 +127,10 @@ size_t bsga_attn_workspace_bytes(int dtype, int heads, int64_t n_tokens, int hea
  *   kv_idx   [heads, nb, idx_stride] int32, each row's kept key blocks: distinct, in [0, nb);
  *   kv_cnt   [heads, nb] int32, 1 <= count <= nb (a row with count 0 yields zeros, lse = -inf)
  *   lse      nullable [heads, n_tokens] float32: natural-log sum-exp of each row's kept logits
- *   workspace, workspace_bytes: device scratch of at least bsga_attn_workspace_bytes(...) bytes
- *            (may be NULL / 0 when that is 0); contents are overwritten; calls sharing one
- *            workspace must be stream-ordered.
+ *   workspace, workspace_bytes: device scratch of at least bsga_attn_workspace_bytes(...) bytes;
+ *            contents are overwritten; calls sharing one workspace must be stream-ordered.  May be
+ *            NULL: the query blocks are then launched in index order instead of heaviest first
+ *            (same results, a longer tail when row lengths differ a lot).
  * bf16: products on bf16 MFMA with fp32 accumulation, fp32 online softmax.  softmax_scale > 0.
  * The index lists are trusted to be in range (they come from bsga_select_blocks); block
  * indices are clamped to [0, nb) before use so a corrupt list cannot read out of bounds.

@@ -179,8 +179,10 @@ def _workspace(q: torch.Tensor, workspace: Optional[torch.Tensor]) -> Tuple[Opti
 
 def bsga_sparse_attn(q, k, v, block: int, kv_idx: torch.Tensor, kv_cnt: torch.Tensor,
                      softmax_scale: Optional[float] = None, return_lse: bool = False,
-                     out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
-    """Attention of each query block over its kept key blocks; returns O (and lse)."""
+                     out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                     ordered: bool = True):
+    """Attention of each query block over its kept key blocks; returns O (and lse).
+    ordered = False passes no workspace: rows are launched in index order, not heaviest first."""
     _require(q, "q"); _require(k, "k", q.dtype); _require(v, "v", q.dtype)
     _require(kv_idx, "kv_idx", torch.int32); _require(kv_cnt, "kv_cnt", torch.int32)
     H, N, d = q.shape
@@ -189,7 +191,7 @@ def bsga_sparse_attn(q, k, v, block: int, kv_idx: torch.Tensor, kv_cnt: torch.Te
     if out is None:
         out = torch.empty_like(q)
     lse = torch.empty((H, N), dtype=torch.float32, device=q.device) if return_lse else None
-    workspace, ws_bytes = _workspace(q, workspace)
+    workspace, ws_bytes = _workspace(q, workspace) if ordered else (None, 0)
     _check(lib.bsga_sparse_attn(_ptr(q), _ptr(k), _ptr(v), _dtype_code(q), H, N, d, block, float(softmax_scale),
                                 _ptr(kv_idx), _ptr(kv_cnt), kv_idx.shape[-1], _ptr(out), _ptr(lse),
                                 _ptr(workspace), ws_bytes, _stream(q)))

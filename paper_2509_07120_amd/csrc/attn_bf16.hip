@@ -96,11 +96,117 @@ __device__ __forceinline__ i32x4 make_rsrc(const void* base, unsigned bytes) {
   return r;
 }
 
+// Launch order of the (head, query block) rows.  Rows much longer than the average (more kept key
+// blocks) go first, longest first, so that they do not end up alone at the end of the grid; all
+// other rows keep the natural order (head-major), because workgroups of equal length that start
+// together walk the keys together and share the K/V tiles in L2, and reordering rows of nearly
+// equal length would only break that up.  Counting sort by kOrderClasses classes of kept count /
+// nb; the classes whose lower bound is below 1.4 x the mean count are merged into one.  Four small
+// kernels: per-head class histogram -> merge -> exclusive scan of the [class][head] table ->
+// placement.  Rows of one (class, head) group come out in arbitrary order, which only changes which
+// workgroup computes which row.
+constexpr int kOrderClasses = 32;
+
+__device__ __forceinline__ int order_class(int cnt, int nb) {  // class 0 holds the longest rows
+  const int c = min(max(cnt, 0), nb);
+  return (kOrderClasses - 1) - static_cast<int>((int64_t(c) * (kOrderClasses - 1)) / nb);
+}
+
+__global__ __launch_bounds__(256) void order_hist_kernel(const int32_t* __restrict__ kv_cnt, int nb, int heads,
+                                                         int32_t* __restrict__ table) {
+  __shared__ int bins[kOrderClasses];
+  const int h = blockIdx.x;
+  const int t = threadIdx.x;
+  if (t < kOrderClasses) bins[t] = 0;
+  __syncthreads();
+  for (int I = t; I < nb; I += 256) atomicAdd(&bins[order_class(kv_cnt[int64_t(h) * nb + I], nb)], 1);
+  __syncthreads();
+  if (t < kOrderClasses) table[int64_t(t) * heads + h] = bins[t];
+}
+
+// One workgroup.  Finds the first class c_bulk whose lower bound (31 - c) / 31 is below 1.4 x the
+// mean kept fraction, folds every lighter class into it (table rows c > c_bulk are added to row
+// c_bulk and zeroed) and leaves c_bulk in table[kOrderClasses * heads].
+__global__ __launch_bounds__(256) void order_merge_kernel(int32_t* __restrict__ table, int heads) {
+  __shared__ long long total[kOrderClasses];
+  __shared__ int c_bulk;
+  const int t = threadIdx.x;
+  if (t < kOrderClasses) total[t] = 0;
+  __syncthreads();
+  for (int64_t i = t; i < int64_t(kOrderClasses) * heads; i += 256)
+    atomicAdd(reinterpret_cast<unsigned long long*>(&total[i / heads]), static_cast<unsigned long long>(table[i]));
+  __syncthreads();
+  if (t == 0) {
+    double rows = 0.0, mass = 0.0;  // mass: kept fraction at the middle of each class
+    for (int c = 0; c < kOrderClasses; ++c) {
+      rows += static_cast<double>(total[c]);
+      mass += static_cast<double>(total[c]) * (kOrderClasses - 1 - c + 0.5) / (kOrderClasses - 1);
+    }
+    const double mean = rows > 0.0 ? mass / rows : 1.0;
+    int c = 0;
+    while (c < kOrderClasses - 1 && static_cast<double>(kOrderClasses - 1 - c) / (kOrderClasses - 1) >= 1.4 * mean) ++c;
+    c_bulk = c;
+    table[int64_t(kOrderClasses) * heads] = c;
+  }
+  __syncthreads();
+  const int cb = c_bulk;
+  for (int h = t; h < heads; h += 256) {
+    int sum = 0;
+    for (int c = cb; c < kOrderClasses; ++c) {
+      sum += table[int64_t(c) * heads + h];
+      table[int64_t(c) * heads + h] = 0;
+    }
+    table[int64_t(cb) * heads + h] = sum;
+  }
+}
+
+// in-place exclusive scan of table[0 .. n) by one workgroup
+__global__ __launch_bounds__(1024) void order_scan_kernel(int32_t* __restrict__ table, int64_t n) {
+  __shared__ int part[1024];
+  __shared__ int carry;
+  const int t = threadIdx.x;
+  if (t == 0) carry = 0;
+  __syncthreads();
+  for (int64_t base = 0; base < n; base += 1024) {
+    const int64_t i = base + t;
+    const int x = i < n ? table[i] : 0;
+    part[t] = x;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+      const int add = t >= o ? part[t - o] : 0;
+      __syncthreads();
+      part[t] += add;
+      __syncthreads();
+    }
+    const int before = carry;
+    if (i < n) table[i] = before + part[t] - x;
+    __syncthreads();
+    if (t == 1023) carry = before + part[1023];
+    __syncthreads();
+  }
+}
+
+__global__ __launch_bounds__(256) void order_place_kernel(const int32_t* __restrict__ kv_cnt, int nb, int heads,
+                                                          const int32_t* __restrict__ table,
+                                                          int32_t* __restrict__ order) {
+  __shared__ int next[kOrderClasses];
+  const int h = blockIdx.x;
+  const int t = threadIdx.x;
+  if (t < kOrderClasses) next[t] = table[int64_t(t) * heads + h];
+  const int c_bulk = table[int64_t(kOrderClasses) * heads];
+  __syncthreads();
+  for (int I = t; I < nb; I += 256) {
+    const int pos = atomicAdd(&next[min(order_class(kv_cnt[int64_t(h) * nb + I], nb), c_bulk)], 1);
+    order[pos] = h * nb + I;
+  }
+}
+
 template <int B>
 __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     const unsigned char* __restrict__ q, const unsigned char* __restrict__ k, const unsigned char* __restrict__ v,
     unsigned short* __restrict__ out, float* __restrict__ lse, const int32_t* __restrict__ kv_idx,
-    const int32_t* __restrict__ kv_cnt, int idx_stride, int64_t n_tokens, int nb, float scale_log2) {
+    const int32_t* __restrict__ kv_cnt, const int32_t* __restrict__ order, int idx_stride, int64_t n_tokens, int nb,
+    float scale_log2) {
   constexpr int WQ = B / 64;              // waves along queries (64 rows each)
   constexpr int KW = B / 2;               // keys per wave per tile
   constexpr int NH = KW / 32;             // 32-key sub-tiles per wave per tile
@@ -116,8 +222,12 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   const int g = lane >> 5;
   const int qi = wave % WQ;
   const int kh = wave / WQ;
-  const int I = blockIdx.x;
-  const int h = blockIdx.y;
+  int h = blockIdx.y, I = blockIdx.x;
+  if (order != nullptr) {  // row number blockIdx.y * gridDim.x + blockIdx.x of the launch order
+    const int row = order[int64_t(blockIdx.y) * nb + blockIdx.x];
+    h = min(max(row / nb, 0), static_cast<int>(gridDim.y) - 1);
+    I = min(max(row % nb, 0), nb - 1);
+  }
   const int64_t head_bytes = int64_t(h) * n_tokens * 128;
   const int64_t rowid = int64_t(h) * nb + I;
   // raw buffer views of this head's K and V (byte-addressed, bounds-checked by the hardware)
@@ -598,8 +708,20 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
 int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int64_t n_tokens, int block,
                      float softmax_scale, const int32_t* kv_idx, const int32_t* kv_cnt, int idx_stride, void* out,
                      float* lse, void* workspace, hipStream_t stream) {
-  (void)workspace;
   const int nb = static_cast<int>(ceil_div(n_tokens, block));
+  const int32_t* order = nullptr;
+  // ordering matters only when the grid does not fit the chip at once
+  if (kv_idx != nullptr && workspace != nullptr && int64_t(heads) * nb >= 1024 && int64_t(heads) * nb < (int64_t(1) << 30)) {
+    // workspace: [heads * nb] launch order, then the [classes][heads] table and one more word
+    int32_t* ord = static_cast<int32_t*>(workspace);
+    int32_t* table = ord + int64_t(heads) * nb;
+    hipLaunchKernelGGL(order_hist_kernel, dim3(heads), dim3(256), 0, stream, kv_cnt, nb, heads, table);
+    hipLaunchKernelGGL(order_merge_kernel, dim3(1), dim3(256), 0, stream, table, heads);
+    hipLaunchKernelGGL(order_scan_kernel, dim3(1), dim3(1024), 0, stream, table, int64_t(kOrderClasses) * heads);
+    hipLaunchKernelGGL(order_place_kernel, dim3(heads), dim3(256), 0, stream, kv_cnt, nb, heads, table, ord);
+    if (int rc = check_hip(hipGetLastError(), "bsga bf16 attention (launch order)")) return rc;
+    order = ord;
+  }
   const float scale_log2 = softmax_scale * kLog2e;
   dim3 grid(nb, heads);
   const unsigned char* qp = static_cast<const unsigned char*>(q);
@@ -617,10 +739,10 @@ int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int
   }
   if (block == 64) {
     hipLaunchKernelGGL((attn_bf16_kernel<64>), grid, dim3(128), lds64, stream, qp, kp, vp, op, lse, kv_idx, kv_cnt,
-                       idx_stride, n_tokens, nb, scale_log2);
+                       order, idx_stride, n_tokens, nb, scale_log2);
   } else {
     hipLaunchKernelGGL((attn_bf16_kernel<128>), grid, dim3(256), lds128, stream, qp, kp, vp, op, lse, kv_idx, kv_cnt,
-                       idx_stride, n_tokens, nb, scale_log2);
+                       order, idx_stride, n_tokens, nb, scale_log2);
   }
   return check_hip(hipGetLastError(), "bsga bf16 attention launch");
 }

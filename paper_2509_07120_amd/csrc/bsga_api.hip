@@ -46,9 +46,12 @@ static int check_block(const char* fn, int block) {
 }
 
 static size_t attn_workspace(int dtype, int heads, int64_t n_tokens) {
-  // The current kernels read Q, K and V in place and keep every intermediate on chip.
-  (void)dtype; (void)heads; (void)n_tokens;
-  return 0;
+  // Q, K and V are read in place and every intermediate stays on chip; the only scratch is the
+  // launch order of the (head, query block) rows of the sparse bf16 kernel: one int32 per row, sized
+  // for the smaller block size, plus a [32 classes][heads] table.
+  if (dtype != BSGA_BF16) return 0;
+  return (static_cast<size_t>(heads) * static_cast<size_t>(ceil_div(n_tokens, 64)) + 32u * static_cast<size_t>(heads) + 4u) *
+         sizeof(int32_t);
 }
 
 static int attn_common(const char* fn, const void* q, const void* k, const void* v, int dtype, int heads,
@@ -70,9 +73,8 @@ static int attn_common(const char* fn, const void* q, const void* k, const void*
       return fail(BSGA_ERR_INVALID_ARG, "%s: idx_stride (%d) must be >= number of key blocks (%lld)", fn, idx_stride,
                   (long long)nb);
   }
-  const size_t need = attn_workspace(dtype, heads, n_tokens);
-  if (need > 0) {
-    if (!workspace) return fail(BSGA_ERR_WORKSPACE, "%s: workspace is null, %zu bytes needed", fn, need);
+  const size_t need = kv_idx ? attn_workspace(dtype, heads, n_tokens) : 0;  // the dense kernel needs none
+  if (need > 0 && workspace) {  // without a workspace the rows are launched in index order
     if (workspace_bytes < need)
       return fail(BSGA_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", fn, workspace_bytes, need);
     if (!aligned16(workspace)) return fail(BSGA_ERR_INVALID_ARG, "%s: workspace must be 16-byte aligned", fn);

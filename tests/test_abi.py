@@ -110,9 +110,10 @@ def test_attention_argument_errors(B):
 
 
 def test_workspace_size(B):
-    """The kernels keep every intermediate on chip: no workspace for any shape."""
+    """Attention keeps every intermediate on chip; the sparse bf16 kernel wants 4 bytes per query block."""
     import torch
-    assert B.bsga_attn_workspace_bytes(torch.bfloat16, 16, 137400) == 0
+    assert B.bsga_attn_workspace_bytes(torch.bfloat16, 16, 137400) == (16 * 2147 + 32 * 16 + 4) * 4
+    assert B.bsga_attn_workspace_bytes(torch.float32, 16, 137400) == 0
     # selection keeps the float64 block logits between its two kernels
     assert B.bsga_select_workspace_bytes(16, 1074, 1074) == 16 * 1074 * 1074 * 8
     assert B.bsga_select_workspace_bytes(0, 10, 10) == 0
