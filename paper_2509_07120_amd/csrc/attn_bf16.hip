@@ -27,8 +27,9 @@
 // the weights as exp2 of the raw scaled logits, i.e. with reference 0 for every row: any reference
 // gives the same O / l, the choice only matters for range, and the range is checked afterwards
 // (see pass()).  Only if that check fails is the workgroup repeated with a running reference
-// maximum (SAFE pass).  Row sums are taken from the bf16-rounded weights (dot2 with ones), i.e.
-// from exactly what multiplies V.
+// maximum (SAFE pass).  Row sums are taken from the fp32 weights; V is multiplied by their bf16
+// roundings, so numerator and denominator differ by at most one bf16 rounding (2^-9 relative),
+// the same size as rounding the output itself.
 #include <stdio.h>
 #include <stdlib.h>
 
@@ -362,13 +363,14 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
       }
   };
 
-  const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
-  // weights of key pair j (registers 2j, 2j+1) of a score block: exp2, round to bf16, add to the
-  // row sum, store as word j of the two B operands
+  // weights of key pair j (registers 2j, 2j+1) of a score block: exp2, add to the row sum, round to
+  // bf16, store as word j of the two B operands.  The row sum takes the fp32 weights with two plain
+  // adds: on this part a dot2 of the packed pair costs four times as much as an add and, unlike the
+  // exp2 and the adds, does not run beside the matrix pipe.
   auto weigh_pair = [&](const f32x16& sc, u32x4 (&w)[2], float& lsum, int j) {
-    const unsigned pk = pack_bf16(__builtin_amdgcn_exp2f(sc[2 * j]), __builtin_amdgcn_exp2f(sc[2 * j + 1]));
-    lsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, lsum, false);
-    w[j >> 2][j & 3] = pk;
+    const float e0 = __builtin_amdgcn_exp2f(sc[2 * j]), e1 = __builtin_amdgcn_exp2f(sc[2 * j + 1]);
+    lsum += e0 + e1;
+    w[j >> 2][j & 3] = pack_bf16(e0, e1);
   };
 
   // ---------------------------------------------------------------------------------------------
@@ -452,7 +454,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   // ---------------------------------------------------------------------------------------------
   // Fast pass for block 128: the same arithmetic as plain_loop<SAFE = false>, software pipelined
   // inside the wave.  A unit is (32-key sub-tile u, query half b): scores QK (4 MFMAs into 16
-  // registers), weights W (16 exp2, 8 packs, 8 dot2), O update PV (4 MFMAs).  A tile has four units
+  // registers), weights W (16 exp2, 8 packs, 16 adds), O update PV (4 MFMAs).  A tile has four units
   // n = 0..3 = (u0,b0), (u0,b1), (u1,b0), (u1,b1).  While the VALU works on W(n) the matrix pipe gets
   // QK(n+1) and PV(n-1), one MFMA per four VALU instructions, so the wave's VALU and MFMA streams
   // overlap instead of waiting for each other.  K operands of a sub-tile serve two units, V operands
@@ -502,7 +504,8 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
           0, 0);                                                                                               \
     }                                                                                                          \
     /* weights, staggered by one slot so that no instruction waits for the one just before it:   */          \
-    /* pack pair S_ (exponentiated in the previous slot), exponentiate the next pair, then sum.  */          \
+    /* pack pair S_ (exponentiated in the previous slot), exponentiate the next pair, then sum   */          \
+    /* pair S_ (two fp32 adds).                                                                  */          \
     {                                                                                                          \
       const unsigned pk = pack_bf16(ex[(S_) & 1][0], ex[(S_) & 1][1]);                                         \
       if constexpr ((S_) < 7) {                                                                                \
@@ -513,7 +516,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
         ex[0][1] = __builtin_amdgcn_exp2f(sc[BN][1]);                                                          \
       }                                                                                                        \
       __builtin_amdgcn_sched_barrier(0);                                                                       \
-      l_run[BQ] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, l_run[BQ], false);     \
+      l_run[BQ] += ex[(S_) & 1][0] + ex[(S_) & 1][1];                                                          \
       pw[BQ][(S_) >> 2][(S_) & 3] = pk;                                                                        \
     }                                                                                                          \
     mid(Int<(S_)>{});                                                                                          \
