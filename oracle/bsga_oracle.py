@@ -150,12 +150,14 @@ def select_blocks(
 
 
 def predict_mask(q, k, b: int, tau: float, rho: float, score_scale: Optional[float] = None,
-                 force_q=None, force_k=None) -> np.ndarray:
-    """Steps 1-4 chained: Q, K [H, N, d] -> block mask."""
+                 force_q=None, force_k=None, b_k: Optional[int] = None) -> np.ndarray:
+    """Steps 1-4 chained: Q, K [H, N, d] -> block mask.  b_k, if given, is a separate block size
+    for the keys (the appendix's learned-projection ablation pools queries by 128 and keys by 64);
+    the mask is then [H, ceil(N/b), ceil(N/b_k)]."""
     d = np.asarray(q).shape[-1]
     if score_scale is None:
         score_scale = 1.0 / math.sqrt(d)
-    probs = block_softmax(block_logits(pool_blocks(q, b), pool_blocks(k, b), score_scale))
+    probs = block_softmax(block_logits(pool_blocks(q, b), pool_blocks(k, b if b_k is None else b_k), score_scale))
     return select_blocks(probs, tau, rho, force_q, force_k)
 
 
@@ -193,8 +195,12 @@ def sparse_attention(
     q_blocks: Optional[Iterable[int]] = None,
     heads: Optional[Sequence[int]] = None,
     return_lse: bool = False,
+    b_k: Optional[int] = None,
 ):
     """Eq. (2) with excluded (not zeroed) masked entries.
+
+    b is the query block size; key blocks have size b_k (default b), so mask is
+    [H, ceil(N/b), ceil(N/b_k)].
 
     For token i of query block I the softmax runs over exactly the keys j < N
     that lie in key blocks J with mask[h, I, J] set; o_i is the resulting
@@ -210,6 +216,8 @@ def sparse_attention(
     H, N, d = q.shape
     scale = 1.0 / math.sqrt(d) if softmax_scale is None else softmax_scale
     nbq = num_blocks(N, b)
+    bk = b if b_k is None else b_k
+    assert mask.shape == (H, nbq, num_blocks(N, bk))
     out = np.full((H, N, d), np.nan, dtype=np.float64)
     lse = np.full((H, N), np.nan, dtype=np.float64)
     head_list = range(H) if heads is None else heads
@@ -218,7 +226,7 @@ def sparse_attention(
         for I in block_list:
             rows = slice(I * b, min((I + 1) * b, N))
             kept = np.flatnonzero(mask[h, I])
-            cols = np.concatenate([np.arange(J * b, min((J + 1) * b, N)) for J in kept])
+            cols = np.concatenate([np.arange(J * bk, min((J + 1) * bk, N)) for J in kept])
             logits = scale * (q[h, rows] @ k[h, cols].T)
             m = logits.max(axis=1, keepdims=True)
             e = np.exp(logits - m)

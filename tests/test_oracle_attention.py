@@ -143,3 +143,39 @@ def test_whole_layer_tau_one_is_dense():
     o, m = O.sparse_global_attention(q, k, v, b, 1.0, 1.0)
     assert m.all()
     np.testing.assert_allclose(o, O.dense_attention(q, k, v), atol=1e-12)
+
+
+# --------------------------------------------------------------------------- separate q / k block sizes
+def test_asymmetric_blocks_token_level_brute_force():
+    """Query blocks of 8, key blocks of 4: every row against a literal masked softmax."""
+    rng = np.random.default_rng(11)
+    H, N, d, bq, bk = 2, 27, 4, 8, 4
+    q, k, v = (rng.standard_normal((H, N, d)) for _ in range(3))
+    q *= 2.0
+    mask = O.predict_mask(q, k, bq, 0.6, 1.0, b_k=bk)
+    assert mask.shape == (H, 4, 7) and not mask.all()
+    out = O.sparse_attention(q, k, v, mask, bq, b_k=bk)
+    for h in range(H):
+        allowed = np.zeros((N, N), dtype=bool)
+        for i in range(N):
+            for j in range(N):
+                allowed[i, j] = mask[h, i // bq, j // bk]
+        logits = (q[h] @ k[h].T) / np.sqrt(d)
+        logits[~allowed] = -np.inf
+        w = np.exp(logits - logits.max(axis=1, keepdims=True))
+        np.testing.assert_allclose(out[h], (w / w.sum(axis=1, keepdims=True)) @ v[h], rtol=0, atol=1e-12)
+
+
+def test_asymmetric_blocks_keep_all_is_dense_and_pooling_is_per_side():
+    rng = np.random.default_rng(12)
+    H, N, d = 1, 40, 8
+    q, k, v = (rng.standard_normal((H, N, d)) for _ in range(3))
+    full = np.ones((H, 3, 5), dtype=bool)
+    np.testing.assert_allclose(O.sparse_attention(q, k, v, full, 16, b_k=8), O.dense_attention(q, k, v), rtol=0, atol=1e-12)
+    # the block scores are the means of the explicit token scores of each (16 x 8) rectangle
+    logits = O.block_logits(O.pool_blocks(q, 16), O.pool_blocks(k, 8), 1.0)
+    s = q[0] @ k[0].T
+    for I in range(3):
+        for J in range(5):
+            want = s[I * 16:min((I + 1) * 16, N), J * 8:(J + 1) * 8].mean()
+            assert abs(logits[0, I, J] - want) < 1e-12
