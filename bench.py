@@ -27,17 +27,20 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0
 
 
-def kept_flops(kv_idx, kv_cnt, n_tokens: int, block: int) -> float:
-    """4 * n_I * n_J * 64 summed over kept pairs, with n_I, n_J the valid tokens of each block."""
+def kept_flops(kv_idx, kv_cnt, n_tokens: int, block: int, block_k: int = 0) -> float:
+    """4 * n_I * n_J * 64 summed over kept pairs, with n_I, n_J the valid tokens of each block
+    (query blocks of `block` tokens, key blocks of `block_k`, default the same)."""
     import torch
+    block_k = block_k or block
     H, nb, _ = kv_idx.shape
-    tail = n_tokens - (nb - 1) * block
+    nbk = -(-n_tokens // block_k)
+    tail_k = n_tokens - (nbk - 1) * block_k
     cnt = kv_cnt.to(torch.int64)
     ar = torch.arange(kv_idx.shape[-1], device=kv_idx.device)[None, None, :]
-    has_last = ((kv_idx == nb - 1) & (ar < cnt[..., None])).any(-1)
-    keys = cnt * block - has_last.to(torch.int64) * (block - tail)          # valid keys per row
+    has_last = ((kv_idx == nbk - 1) & (ar < cnt[..., None])).any(-1)
+    keys = cnt * block_k - has_last.to(torch.int64) * (block_k - tail_k)     # valid keys per row
     rows = torch.full((nb,), block, device=kv_idx.device, dtype=torch.int64)
-    rows[-1] = tail
+    rows[-1] = n_tokens - (nb - 1) * block
     return float((keys * rows[None, :]).sum().item()) * 4.0 * 64.0
 
 
@@ -112,6 +115,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     ap.add_argument("--sweep", action="store_true", help="also time the (tau, rho) sweep; rows go to stderr and into the JSON")
+    ap.add_argument("--asym", action="store_true",
+                    help="also time the layer with query blocks of 128 and key blocks of 64; goes into the JSON")
     ap.add_argument("--special", action="store_true",
                     help="also time the layer with the special-token split (gathers included); goes into the JSON")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -210,6 +215,41 @@ def main() -> int:
             sweep_rows.append(row)
             print("[sweep] " + json.dumps(row), file=sys.stderr, flush=True)
 
+    asym_rows = []
+    if args.asym and b == 128:
+        nbk64 = -(-N // 64)
+        ws64 = torch.empty(B.bsga_select_workspace_bytes(H, cfg.n_blocks, nbk64), dtype=torch.uint8, device="cuda")
+        for tau, rho in [(args.tau, args.rho), (0.0, 0.5), (0.0, 0.75), (0.0, 0.9)]:
+            def asym_layer(ev=None):
+                if ev:
+                    ev[0].record()
+                qp, kp = B.bsga_pool(tq, 128), B.bsga_pool(tk, 64)
+                _, idx, cnt = B.bsga_select_blocks(qp, kp, tau, rho, want_bits=False, workspace=ws64)
+                if ev:
+                    ev[1].record()
+                B.bsga_sparse_attn(tq, tk, tv, 128, idx, cnt, out=out, workspace=ws, block_k=64)
+                if ev:
+                    ev[2].record()
+                return idx, cnt
+            asym_layer()
+            torch.cuda.synchronize()
+            steps = max(2, args.steps // 2)
+            evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+            t0 = time.perf_counter()
+            for s_ in range(steps):
+                idx, cnt = asym_layer(evs[s_])
+            torch.cuda.synchronize()
+            w = (time.perf_counter() - t0) * 1e3 / steps
+            st = [sum(e[i].elapsed_time(e[i + 1]) for e in evs) / steps for i in range(2)]
+            fl = kept_flops(idx, cnt, N, 128, 64)
+            kf = float(cnt.to(torch.float64).sum().item()) / (H * cfg.n_blocks * nbk64)
+            row = {"tau": tau, "rho": rho, "block_q": 128, "block_k": 64, "kept_fraction": kf, "layer_ms": w,
+                   "pool_select_ms": st[0], "attention_ms": st[1], "kept_tflops_layer": fl / (w * 1e-3) / 1e12,
+                   "speedup_vs_dense": (dense_ms / w) if dense_ms else None}
+            asym_rows.append(row)
+            print("[asym] " + json.dumps(row), file=sys.stderr, flush=True)
+        del ws64
+
     special_rec = None
     if args.special:
         # Sec. 4.2: patch tokens first, special tokens last; block map on the pure patch blocks only
@@ -297,6 +337,8 @@ def main() -> int:
         rec["sweep"] = sweep_rows
     if special_rec:
         rec["special_token_split"] = special_rec
+    if asym_rows:
+        rec["query128_key64_blocks"] = asym_rows
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(cfg, args.tau, args.cpu_budget)
     print(json.dumps(rec), flush=True)

@@ -141,6 +141,20 @@ int bsga_sparse_attn(const void* q, const void* k, const void* v, int dtype, int
                      float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Block-sparse attention with separate query and key block sizes (the appendix's learned-projection
+ * ablation predicts its maps with query blocks of 128 and key blocks of 64; Sec. 4.1 otherwise).
+ * As bsga_sparse_attn, but query block I covers block_q tokens and the lists refer to key blocks of
+ * block_k tokens: kv_idx [heads, ceil(n_tokens/block_q), idx_stride] with entries in
+ * [0, ceil(n_tokens/block_k)), idx_stride >= ceil(n_tokens/block_k).
+ * Supported: block_k == block_q (64 or 128), and block_q = 128 with block_k = 64 (bf16 only; pool Q
+ * and K separately with bsga_pool_qk, select with nb_q != nb_k).  Other pairs: BSGA_ERR_UNSUPPORTED.
+ */
+int bsga_sparse_attn_qk(const void* q, const void* k, const void* v, int dtype, int heads,
+                        int64_t n_tokens, int head_dim, int block_q, int block_k, float softmax_scale,
+                        const int32_t* kv_idx, const int32_t* kv_cnt, int idx_stride, void* out,
+                        float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Dense attention baseline  (Sec. 4.1, Eq. (1)): softmax(softmax_scale * Q K^T) V per head.
  * Same tensors, workspace and numerics as bsga_sparse_attn, every key visible.
  */

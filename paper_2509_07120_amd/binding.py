@@ -36,6 +36,7 @@ EXPORTED_SYMBOLS = (
     "bsga_gather_tokens",
     "bsga_attn_workspace_bytes",
     "bsga_sparse_attn",
+    "bsga_sparse_attn_qk",
     "bsga_dense_attn",
 )
 
@@ -74,6 +75,9 @@ def _load() -> ctypes.CDLL:
     lib.bsga_sparse_attn.restype = c_int
     lib.bsga_sparse_attn.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int64, c_int, c_int, c_float,
                                      c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.bsga_sparse_attn_qk.restype = c_int
+    lib.bsga_sparse_attn_qk.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int64, c_int, c_int, c_int, c_float,
+                                        c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     lib.bsga_dense_attn.restype = c_int
     lib.bsga_dense_attn.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int64, c_int, c_float,
                                     c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
@@ -130,6 +134,15 @@ def bsga_pool_qk(q: torch.Tensor, k: torch.Tensor, block: int) -> Tuple[torch.Te
     return q_pool, k_pool
 
 
+def bsga_pool(x: torch.Tensor, block: int) -> torch.Tensor:
+    """x [H, N, 64] -> block means [H, ceil(N/block), 64] float64 (one tensor; for separate q / k block sizes)."""
+    _require(x, "x")
+    H, N, d = x.shape
+    pooled = torch.empty((H, num_blocks(N, block), d), dtype=torch.float64, device=x.device)
+    _check(lib.bsga_pool_qk(_ptr(x), None, _dtype_code(x), H, N, d, block, _ptr(pooled), None, _stream(x)))
+    return pooled
+
+
 def bsga_select_blocks(q_pool: torch.Tensor, k_pool: torch.Tensor, tau: float, rho: float = 1.0,
                        score_scale: Optional[float] = None, force_q: Optional[torch.Tensor] = None,
                        force_k: Optional[torch.Tensor] = None, want_bits: bool = True,
@@ -180,9 +193,10 @@ def _workspace(q: torch.Tensor, workspace: Optional[torch.Tensor]) -> Tuple[Opti
 def bsga_sparse_attn(q, k, v, block: int, kv_idx: torch.Tensor, kv_cnt: torch.Tensor,
                      softmax_scale: Optional[float] = None, return_lse: bool = False,
                      out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                     ordered: bool = True):
+                     ordered: bool = True, block_k: Optional[int] = None):
     """Attention of each query block over its kept key blocks; returns O (and lse).
-    ordered = False passes no workspace: rows are launched in index order, not heaviest first."""
+    ordered = False passes no workspace: rows are launched in index order, not heaviest first.
+    block_k: size of the key blocks the lists refer to when it differs from the query block size."""
     _require(q, "q"); _require(k, "k", q.dtype); _require(v, "v", q.dtype)
     _require(kv_idx, "kv_idx", torch.int32); _require(kv_cnt, "kv_cnt", torch.int32)
     H, N, d = q.shape
@@ -192,9 +206,14 @@ def bsga_sparse_attn(q, k, v, block: int, kv_idx: torch.Tensor, kv_cnt: torch.Te
         out = torch.empty_like(q)
     lse = torch.empty((H, N), dtype=torch.float32, device=q.device) if return_lse else None
     workspace, ws_bytes = _workspace(q, workspace) if ordered else (None, 0)
-    _check(lib.bsga_sparse_attn(_ptr(q), _ptr(k), _ptr(v), _dtype_code(q), H, N, d, block, float(softmax_scale),
-                                _ptr(kv_idx), _ptr(kv_cnt), kv_idx.shape[-1], _ptr(out), _ptr(lse),
-                                _ptr(workspace), ws_bytes, _stream(q)))
+    if block_k is None or block_k == block:
+        _check(lib.bsga_sparse_attn(_ptr(q), _ptr(k), _ptr(v), _dtype_code(q), H, N, d, block, float(softmax_scale),
+                                    _ptr(kv_idx), _ptr(kv_cnt), kv_idx.shape[-1], _ptr(out), _ptr(lse),
+                                    _ptr(workspace), ws_bytes, _stream(q)))
+    else:
+        _check(lib.bsga_sparse_attn_qk(_ptr(q), _ptr(k), _ptr(v), _dtype_code(q), H, N, d, block, block_k,
+                                       float(softmax_scale), _ptr(kv_idx), _ptr(kv_cnt), kv_idx.shape[-1], _ptr(out),
+                                       _ptr(lse), _ptr(workspace), ws_bytes, _stream(q)))
     return (out, lse) if return_lse else out
 
 

@@ -113,14 +113,14 @@ __device__ __forceinline__ int order_class(int cnt, int nb) {  // class 0 holds 
   return (kOrderClasses - 1) - static_cast<int>((int64_t(c) * (kOrderClasses - 1)) / nb);
 }
 
-__global__ __launch_bounds__(256) void order_hist_kernel(const int32_t* __restrict__ kv_cnt, int nb, int heads,
-                                                         int32_t* __restrict__ table) {
+__global__ __launch_bounds__(256) void order_hist_kernel(const int32_t* __restrict__ kv_cnt, int nb, int nbk,
+                                                         int heads, int32_t* __restrict__ table) {
   __shared__ int bins[kOrderClasses];
   const int h = blockIdx.x;
   const int t = threadIdx.x;
   if (t < kOrderClasses) bins[t] = 0;
   __syncthreads();
-  for (int I = t; I < nb; I += 256) atomicAdd(&bins[order_class(kv_cnt[int64_t(h) * nb + I], nb)], 1);
+  for (int I = t; I < nb; I += 256) atomicAdd(&bins[order_class(kv_cnt[int64_t(h) * nb + I], nbk)], 1);
   __syncthreads();
   if (t < kOrderClasses) table[int64_t(t) * heads + h] = bins[t];
 }
@@ -187,8 +187,8 @@ __global__ __launch_bounds__(1024) void order_scan_kernel(int32_t* __restrict__ 
   }
 }
 
-__global__ __launch_bounds__(256) void order_place_kernel(const int32_t* __restrict__ kv_cnt, int nb, int heads,
-                                                          const int32_t* __restrict__ table,
+__global__ __launch_bounds__(256) void order_place_kernel(const int32_t* __restrict__ kv_cnt, int nb, int nbk,
+                                                          int heads, const int32_t* __restrict__ table,
                                                           int32_t* __restrict__ order) {
   __shared__ int next[kOrderClasses];
   const int h = blockIdx.x;
@@ -197,17 +197,28 @@ __global__ __launch_bounds__(256) void order_place_kernel(const int32_t* __restr
   const int c_bulk = table[int64_t(kOrderClasses) * heads];
   __syncthreads();
   for (int I = t; I < nb; I += 256) {
-    const int pos = atomicAdd(&next[min(order_class(kv_cnt[int64_t(h) * nb + I], nb), c_bulk)], 1);
+    const int pos = atomicAdd(&next[min(order_class(kv_cnt[int64_t(h) * nb + I], nbk), c_bulk)], 1);
     order[pos] = h * nb + I;
   }
 }
 
-template <int B>
+// A key tile of B keys in LDS.  With key blocks of B keys it is one listed block (a); with key blocks
+// of B/2 keys it is two consecutive entries of the row's list, one per half (b < 0: the list ended,
+// the second half is empty).
+struct Tile {
+  int a, b;
+};
+
+// B: query rows per workgroup = keys per LDS tile.  KB: size of the key blocks the index list refers
+// to, B or B/2.
+template <int B, int KB>
 __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     const unsigned char* __restrict__ q, const unsigned char* __restrict__ k, const unsigned char* __restrict__ v,
     unsigned short* __restrict__ out, float* __restrict__ lse, const int32_t* __restrict__ kv_idx,
     const int32_t* __restrict__ kv_cnt, const int32_t* __restrict__ order, int idx_stride, int64_t n_tokens, int nb,
-    float scale_log2) {
+    int nbk, float scale_log2) {
+  static_assert(KB == B || (2 * KB == B && B == 128), "key blocks are whole tiles or half tiles of 128");
+  constexpr bool HALF = KB != B;          // two listed key blocks per tile
   constexpr int WQ = B / 64;              // waves along queries (64 rows each)
   constexpr int KW = B / 2;               // keys per wave per tile
   constexpr int NH = KW / 32;             // 32-key sub-tiles per wave per tile
@@ -303,9 +314,10 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   float l_run[2];  // this lane's share of the row sums
 
   const bool dense = kv_idx == nullptr;
-  const int count = dense ? nb : min(max(kv_cnt[rowid], 0), nb);
+  const int count = dense ? nbk : min(max(kv_cnt[rowid], 0), nbk);  // listed key blocks
+  const int ntiles = HALF ? (count + 1) >> 1 : count;
   const int32_t* my_idx = dense ? nullptr : kv_idx + rowid * idx_stride;
-  const int tail = static_cast<int>(n_tokens - int64_t(nb - 1) * B);  // valid keys in the last tile
+  const int tail = static_cast<int>(n_tokens - int64_t(nbk - 1) * KB);  // valid keys in the last key block
 
   // The row's key-block list is read 64 entries at a time, one per lane, and handed out with
   // readlane; the next 64 are already in flight while the current ones are consumed.
@@ -314,30 +326,59 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     const int t = first + lane;
     return (!dense && t < count) ? my_idx[t] : 0;
   };
-  auto block_at = [&](int it) {  // must be called with it = 0, 1, 2, ... in order
-    if (dense) return it;
-    if (it > 0 && (it & 63) == 0) {
+  auto block_at = [&](int it) -> Tile {  // tile number it; must be called with it = 0, 1, 2, ... in order
+    if (dense) return Tile{it, -1};
+    constexpr int PER = HALF ? 2 : 1;  // list entries per tile
+    const int e = it * PER;
+    if (it > 0 && (e & 63) == 0) {
       idx_cur = idx_next;
-      idx_next = load_idx(it + 64);
+      idx_next = load_idx(e + 64);
     }
-    const int J = __builtin_amdgcn_readlane(idx_cur, it & 63);
-    return min(max(J, 0), nb - 1);
+    const int ja = __builtin_amdgcn_readlane(idx_cur, e & 63);
+    Tile t{min(max(ja, 0), nbk - 1), -1};
+    if constexpr (HALF) {
+      const int jb = __builtin_amdgcn_readlane(idx_cur, (e + 1) & 63);
+      if (e + 1 < count) t.b = min(max(jb, 0), nbk - 1);
+    }
+    return t;
+  };
+  // valid keys in half `half` of a tile (whole tile if !HALF): the last key block may be ragged
+  auto valid_keys = [&](const Tile& t, int half) {
+    const int J = (HALF && half == 1) ? t.b : t.a;
+    if (J < 0) return 0;
+    return (J == nbk - 1) ? tail : KB;
+  };
+  auto padded_keys = [&](const Tile& t) {  // keys of the tile that do not exist (zero-filled in LDS)
+    return HALF ? (2 * KB - valid_keys(t, 0) - valid_keys(t, 1)) : (B - valid_keys(t, 0));
   };
   // Direct-to-LDS load number i2 (0..7) of key tile J into buffer pair `buf`: even i2 moves 1 KB of
   // the K tile, odd i2 1 KB of the V tile.  Rows of a ragged last tile that lie past the end of the
   // head's buffer fail the hardware bounds check, which makes the load write zeros for them.
-  auto issue_part = [&](int J, int buf, int i2) {
+  // With half-tile key blocks, loads i = 0, 1 fill tile rows 0..63 from block a and i = 2, 3 rows
+  // 64..127 from block b; an absent b gets an offset past the end of the buffer, so the bounds check
+  // zero-fills that half.
+  auto issue_part = [&](const Tile& J, int buf, int i2) {
     const int i = i2 >> 1;
     const bool is_v = (i2 & 1) != 0;
-    const unsigned soff = static_cast<unsigned>(J) * TILE_BYTES;
     const unsigned dst = smem_addr + wave * 1024 + NW * i * 1024 + (is_v ? V_BASE : 0) + buf * TILE_BYTES;
-    if (is_v) {
-      dma16(vrsrc, voff, soff + i * NW * 1024, dst);
+    if constexpr (HALF) {
+      const int Jx = (i >> 1) ? J.b : J.a;
+      const unsigned soff = Jx < 0 ? head_size : static_cast<unsigned>(Jx) * (KB * 128);
+      if (is_v) {
+        dma16(vrsrc, voff, soff + (Jx < 0 ? 0u : (i & 1) * NW * 1024), dst);
+      } else {
+        dma16(krsrc, koff[i % KN], soff, dst);
+      }
     } else {
-      dma16(krsrc, koff[i % KN], soff + (i / KN) * KN * NW * 1024, dst);
+      const unsigned soff = static_cast<unsigned>(J.a) * TILE_BYTES;
+      if (is_v) {
+        dma16(vrsrc, voff, soff + i * NW * 1024, dst);
+      } else {
+        dma16(krsrc, koff[i % KN], soff + (i / KN) * KN * NW * 1024, dst);
+      }
     }
   };
-  auto issue = [&](int J, int buf) {
+  auto issue = [&](const Tile& J, int buf) {
 #pragma unroll
     for (int i2 = 0; i2 < 8; ++i2) issue_part(J, buf, i2);
   };
@@ -384,18 +425,20 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   //   exactly 2^0 = 1 to the row sum and nothing to O; pass() subtracts their count.
   auto plain_loop = [&](auto safec, int& pad_keys) {
     constexpr bool SAFE = decltype(safec)::value;
-    if (count <= 0) return;
-    int J_cur = block_at(0);
+    if (ntiles <= 0) return;
+    Tile J_cur = block_at(0);
     issue(J_cur, 0);
-    for (int it = 0; it < count; ++it) {
+    for (int it = 0; it < ntiles; ++it) {
       const int buf = it & 1;
-      const int J_next = (it + 1 < count) ? block_at(it + 1) : 0;
+      const Tile J_next = (it + 1 < ntiles) ? block_at(it + 1) : Tile{0, -1};
       __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile `it` has landed
       __syncthreads();                     // ... and so has everyone else's; buffer buf^1 is free
-      if (it + 1 < count) issue(J_next, buf ^ 1);
+      if (it + 1 < ntiles) issue(J_next, buf ^ 1);
       const unsigned boff = buf * TILE_BYTES;
-      const bool ragged = (J_cur == nb - 1 && tail < B);
-      if (ragged && !SAFE) pad_keys += B - tail;
+      const bool ragged = padded_keys(J_cur) > 0;
+      if (ragged && !SAFE) pad_keys += padded_keys(J_cur);
+      // first key of the tile (counted from the tile's start) that this wave must mask in SAFE mode
+      const int limit = HALF ? kh * KW + valid_keys(J_cur, kh) : valid_keys(J_cur, 0);
 #pragma unroll
       for (int u = 0; u < NH; ++u) {
         bf16x8 ka[4], va[2][2];
@@ -414,7 +457,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
 #pragma unroll
               for (int i = 0; i < 16; ++i) {
                 const int key = kh * KW + u * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-                if (key >= tail) sc[i] = -INFINITY;
+                if (key >= limit) sc[i] = -INFINITY;
               }
             }
             float tmax = -INFINITY;
@@ -464,7 +507,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   // after the last score MFMA of this tile) and the current buffers are free, so the eight loads of
   // the tile after next are issued into them, one after each of the following MFMAs.
   auto fast_loop = [&](int& pad_keys) {
-    if (count <= 0) return;
+    if (ntiles <= 0) return;
     f32x16 sc[2];        // scores: [query half]
     u32x4 pw[2][2];      // weights as packed bf16 pairs: [query half][16-key chunk]
     bf16x8 ka[4];        // K operands of the sub-tile whose scores are computed next
@@ -529,9 +572,9 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     // a whole tile in buffer pair `buf` (byte offset boff; the other pair is at boff ^ TILE_BYTES).
     // On entry: sc[0] = QK(0) of this tile, ka = K operands of sub-tile 0, pw[1] / va[1] = weights /
     // V operands of the previous tile's unit 3 (zeros before the first tile).
-    auto tile = [&](auto hasnextc, int J, int J_next2, int buf) {
+    auto tile = [&](auto hasnextc, const Tile& J, const Tile& J_next2, int buf) {
       constexpr bool has_next = decltype(hasnextc)::value;
-      if (J == nb - 1 && tail < B) pad_keys += B - tail;
+      pad_keys += padded_keys(J);
       const unsigned boff = buf * TILE_BYTES;
       unit(Int<0>{}, std::true_type{}, [&](auto slot) {  // QK(1); K(u1); PV(previous 3); V(u0)
         constexpr int S = decltype(slot)::value;
@@ -558,10 +601,10 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     };
 
     // ---- prologue: tiles 0 and 1 on their way, K operands of sub-tile 0, QK(0) ----------------------
-    int J_cur = block_at(0);
+    Tile J_cur = block_at(0);
     issue(J_cur, 0);
-    int J_nxt = J_cur;
-    if (count > 1) {
+    Tile J_nxt = J_cur;
+    if (ntiles > 1) {
       J_nxt = block_at(1);
       issue(J_nxt, 1);
     }
@@ -579,15 +622,15 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- all tiles but the last --------------------------------------------------------------------
-    for (int T = 0; T + 1 < count; ++T) {
+    for (int T = 0; T + 1 < ntiles; ++T) {
       // the tile after next; at the end of the list one more (harmless) load of a valid tile
-      const int J2 = (T + 2 < count) ? block_at(T + 2) : J_cur;
+      const Tile J2 = (T + 2 < ntiles) ? block_at(T + 2) : J_cur;
       tile(std::true_type{}, J_cur, J2, T & 1);
       J_cur = J_nxt;
       J_nxt = J2;
     }
     // ---- the last tile, then the O update of its last unit -----------------------------------------
-    tile(std::false_type{}, J_cur, J_cur, (count - 1) & 1);
+    tile(std::false_type{}, J_cur, J_cur, (ntiles - 1) & 1);
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
@@ -709,19 +752,20 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
 }  // namespace
 
 int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int64_t n_tokens, int block,
-                     float softmax_scale, const int32_t* kv_idx, const int32_t* kv_cnt, int idx_stride, void* out,
-                     float* lse, void* workspace, hipStream_t stream) {
-  const int nb = static_cast<int>(ceil_div(n_tokens, block));
+                     int block_k, float softmax_scale, const int32_t* kv_idx, const int32_t* kv_cnt, int idx_stride,
+                     void* out, float* lse, void* workspace, hipStream_t stream) {
+  const int nb = static_cast<int>(ceil_div(n_tokens, block));     // query blocks
+  const int nbk = static_cast<int>(ceil_div(n_tokens, block_k));  // key blocks the lists refer to
   const int32_t* order = nullptr;
   // ordering matters only when the grid does not fit the chip at once
   if (kv_idx != nullptr && workspace != nullptr && int64_t(heads) * nb >= 1024 && int64_t(heads) * nb < (int64_t(1) << 30)) {
     // workspace: [heads * nb] launch order, then the [classes][heads] table and one more word
     int32_t* ord = static_cast<int32_t*>(workspace);
     int32_t* table = ord + int64_t(heads) * nb;
-    hipLaunchKernelGGL(order_hist_kernel, dim3(heads), dim3(256), 0, stream, kv_cnt, nb, heads, table);
+    hipLaunchKernelGGL(order_hist_kernel, dim3(heads), dim3(256), 0, stream, kv_cnt, nb, nbk, heads, table);
     hipLaunchKernelGGL(order_merge_kernel, dim3(1), dim3(256), 0, stream, table, heads);
     hipLaunchKernelGGL(order_scan_kernel, dim3(1), dim3(1024), 0, stream, table, int64_t(kOrderClasses) * heads);
-    hipLaunchKernelGGL(order_place_kernel, dim3(heads), dim3(256), 0, stream, kv_cnt, nb, heads, table, ord);
+    hipLaunchKernelGGL(order_place_kernel, dim3(heads), dim3(256), 0, stream, kv_cnt, nb, nbk, heads, table, ord);
     if (int rc = check_hip(hipGetLastError(), "bsga bf16 attention (launch order)")) return rc;
     order = ord;
   }
@@ -736,16 +780,19 @@ int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int
   const size_t lds64 = 4 * 64 * 128, lds128 = 4 * 128 * 128;
   if (getenv("BSGA_DEBUG") != nullptr) {
     int n64 = -1, n128 = -1;
-    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n64, attn_bf16_kernel<64>, 128, lds64);
-    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n128, attn_bf16_kernel<128>, 256, lds128);
+    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n64, attn_bf16_kernel<64, 64>, 128, lds64);
+    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&n128, attn_bf16_kernel<128, 128>, 256, lds128);
     fprintf(stderr, "[bsga] attention occupancy (workgroups per CU): block 64 -> %d, block 128 -> %d\n", n64, n128);
   }
   if (block == 64) {
-    hipLaunchKernelGGL((attn_bf16_kernel<64>), grid, dim3(128), lds64, stream, qp, kp, vp, op, lse, kv_idx, kv_cnt,
-                       order, idx_stride, n_tokens, nb, scale_log2);
+    hipLaunchKernelGGL((attn_bf16_kernel<64, 64>), grid, dim3(128), lds64, stream, qp, kp, vp, op, lse, kv_idx,
+                       kv_cnt, order, idx_stride, n_tokens, nb, nbk, scale_log2);
+  } else if (block_k == 128) {
+    hipLaunchKernelGGL((attn_bf16_kernel<128, 128>), grid, dim3(256), lds128, stream, qp, kp, vp, op, lse, kv_idx,
+                       kv_cnt, order, idx_stride, n_tokens, nb, nbk, scale_log2);
   } else {
-    hipLaunchKernelGGL((attn_bf16_kernel<128>), grid, dim3(256), lds128, stream, qp, kp, vp, op, lse, kv_idx, kv_cnt,
-                       order, idx_stride, n_tokens, nb, scale_log2);
+    hipLaunchKernelGGL((attn_bf16_kernel<128, 64>), grid, dim3(256), lds128, stream, qp, kp, vp, op, lse, kv_idx,
+                       kv_cnt, order, idx_stride, n_tokens, nb, nbk, scale_log2);
   }
   return check_hip(hipGetLastError(), "bsga bf16 attention launch");
 }

@@ -55,18 +55,25 @@ static size_t attn_workspace(int dtype, int heads, int64_t n_tokens) {
 }
 
 static int attn_common(const char* fn, const void* q, const void* k, const void* v, int dtype, int heads,
-                       int64_t n_tokens, int head_dim, int block, float softmax_scale,
+                       int64_t n_tokens, int head_dim, int block, int block_k, float softmax_scale,
                        const int32_t* kv_idx, const int32_t* kv_cnt, int idx_stride, void* out, float* lse,
                        void* workspace, size_t workspace_bytes, void* stream) {
   clear_error();
   if (int rc = check_shape(fn, dtype, heads, n_tokens, head_dim)) return rc;
   if (int rc = check_block(fn, block)) return rc;
+  if (block_k != block) {
+    if (!(block == 128 && block_k == 64))
+      return fail(BSGA_ERR_UNSUPPORTED, "%s: key blocks must have the query block size, or 64 with query blocks of 128 (got %d / %d)",
+                  fn, block, block_k);
+    if (dtype != BSGA_BF16)
+      return fail(BSGA_ERR_UNSUPPORTED, "%s: separate query / key block sizes are implemented for bf16 only", fn);
+  }
   if (!q || !k || !v || !out) return fail(BSGA_ERR_INVALID_ARG, "%s: q, k, v and out must be non-null", fn);
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out))
     return fail(BSGA_ERR_INVALID_ARG, "%s: q, k, v and out must be 16-byte aligned", fn);
   if (!(softmax_scale > 0.0f) || !isfinite(softmax_scale))
     return fail(BSGA_ERR_INVALID_ARG, "%s: softmax_scale must be finite and > 0", fn);
-  const int64_t nb = ceil_div(n_tokens, block);
+  const int64_t nb = ceil_div(n_tokens, block_k);
   if (kv_idx || kv_cnt) {
     if (!kv_idx || !kv_cnt) return fail(BSGA_ERR_INVALID_ARG, "%s: kv_idx and kv_cnt must both be given", fn);
     if (idx_stride < nb)
@@ -81,7 +88,7 @@ static int attn_common(const char* fn, const void* q, const void* k, const void*
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (dtype == BSGA_BF16)
-    return launch_attn_bf16(q, k, v, heads, n_tokens, block, softmax_scale, kv_idx, kv_cnt, idx_stride, out, lse,
+    return launch_attn_bf16(q, k, v, heads, n_tokens, block, block_k, softmax_scale, kv_idx, kv_cnt, idx_stride, out, lse,
                             workspace, s);
   return launch_attn_fp32(static_cast<const float*>(q), static_cast<const float*>(k), static_cast<const float*>(v),
                           heads, n_tokens, block, softmax_scale, kv_idx, kv_cnt, idx_stride,
@@ -180,15 +187,27 @@ int bsga_sparse_attn(const void* q, const void* k, const void* v, int dtype, int
     clear_error();
     return fail(BSGA_ERR_INVALID_ARG, "bsga_sparse_attn: kv_idx and kv_cnt must be non-null");
   }
-  return attn_common("bsga_sparse_attn", q, k, v, dtype, heads, n_tokens, head_dim, block, softmax_scale, kv_idx,
-                     kv_cnt, idx_stride, out, lse, workspace, workspace_bytes, stream);
+  return attn_common("bsga_sparse_attn", q, k, v, dtype, heads, n_tokens, head_dim, block, block, softmax_scale,
+                     kv_idx, kv_cnt, idx_stride, out, lse, workspace, workspace_bytes, stream);
+}
+
+int bsga_sparse_attn_qk(const void* q, const void* k, const void* v, int dtype, int heads, int64_t n_tokens,
+                        int head_dim, int block_q, int block_k, float softmax_scale, const int32_t* kv_idx,
+                        const int32_t* kv_cnt, int idx_stride, void* out, float* lse, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+  if (!kv_idx || !kv_cnt) {
+    clear_error();
+    return fail(BSGA_ERR_INVALID_ARG, "bsga_sparse_attn_qk: kv_idx and kv_cnt must be non-null");
+  }
+  return attn_common("bsga_sparse_attn_qk", q, k, v, dtype, heads, n_tokens, head_dim, block_q, block_k,
+                     softmax_scale, kv_idx, kv_cnt, idx_stride, out, lse, workspace, workspace_bytes, stream);
 }
 
 int bsga_dense_attn(const void* q, const void* k, const void* v, int dtype, int heads, int64_t n_tokens,
                     int head_dim, float softmax_scale, void* out, float* lse, void* workspace,
                     size_t workspace_bytes, void* stream) {
   const int block = (dtype == BSGA_FP32) ? 64 : 128;
-  return attn_common("bsga_dense_attn", q, k, v, dtype, heads, n_tokens, head_dim, block, softmax_scale, nullptr,
+  return attn_common("bsga_dense_attn", q, k, v, dtype, heads, n_tokens, head_dim, block, block, softmax_scale, nullptr,
                      nullptr, 0, out, lse, workspace, workspace_bytes, stream);
 }
 

@@ -32,7 +32,7 @@ int launch_gather(const void* src, int dtype, int heads, int64_t n_src, const in
                   int64_t n_dst, void* dst, hipStream_t stream);
 
 int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int64_t n_tokens,
-                     int block, float softmax_scale, const int32_t* kv_idx, const int32_t* kv_cnt,
+                     int block, int block_k, float softmax_scale, const int32_t* kv_idx, const int32_t* kv_cnt,
                      int idx_stride, void* out, float* lse, void* workspace, hipStream_t stream);
 
 int launch_attn_fp32(const float* q, const float* k, const float* v, int heads, int64_t n_tokens,
