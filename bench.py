@@ -115,6 +115,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     ap.add_argument("--sweep", action="store_true", help="also time the (tau, rho) sweep; rows go to stderr and into the JSON")
+    ap.add_argument("--block", action="store_true",
+                    help="also time one whole transformer block (projections + this layer + MLP, d_model 1024, random "
+                         "weights) dense and sparse; goes into the JSON")
     ap.add_argument("--asym", action="store_true",
                     help="also time the layer with query blocks of 128 and key blocks of 64; goes into the JSON")
     ap.add_argument("--special", action="store_true",
@@ -214,6 +217,29 @@ def main() -> int:
                    "bound_end_to_end_speedup": theoretical_speedup(cfg.frames, cfg.tokens_per_frame, 1.0 - kf)}
             sweep_rows.append(row)
             print("[sweep] " + json.dumps(row), file=sys.stderr, flush=True)
+
+    block_rows = []
+    if args.block:
+        flags = torch.arange(N) % cfg.tokens_per_frame < 5
+        gx = torch.Generator().manual_seed(1)
+        x = torch.randn(N, 1024, generator=gx).to(torch.bfloat16).cuda()
+        for name, tau, rho, sp in [("dense", 1.0, 1.0, None), ("tau=0.9", 0.9, 1.0, None), ("tau=0.9, special split", 0.9, 1.0, flags),
+                                   ("top-k rho=0.75, special split", 0.0, 0.75, flags)]:
+            blk = B.GlobalAttentionBlock(1024, H, b, tau, rho, special=sp)
+            blk(x)
+            torch.cuda.synchronize()
+            e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            e0.record()
+            a = blk.attention(x)
+            e1.record()
+            blk(x)
+            e2.record()
+            torch.cuda.synchronize()
+            row = {"variant": name, "attention_with_projections_ms": e0.elapsed_time(e1), "block_ms": e1.elapsed_time(e2)}
+            block_rows.append(row)
+            print("[block] " + json.dumps(row), file=sys.stderr, flush=True)
+            del blk, a
+        del x
 
     asym_rows = []
     if args.asym and b == 128:
@@ -339,6 +365,8 @@ def main() -> int:
         rec["special_token_split"] = special_rec
     if asym_rows:
         rec["query128_key64_blocks"] = asym_rows
+    if block_rows:
+        rec["transformer_block"] = block_rows
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(cfg, args.tau, args.cpu_budget)
     print(json.dumps(rec), flush=True)

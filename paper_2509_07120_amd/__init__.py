@@ -1,4 +1,5 @@
 """Block-sparse global attention for MI355X (gfx950): Python binding of libbsga.so."""
+from .block import GlobalAttentionBlock  # noqa: F401
 from .binding import (  # noqa: F401
     BSGA_BF16,
     BSGA_FP32,
