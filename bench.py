@@ -183,6 +183,8 @@ def main() -> int:
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3 / steps
         stage = [sum(e[i].elapsed_time(e[i + 1]) for e in evs) / steps for i in range(3)]
+        print("[bench] attention ms per step: " + ", ".join(f"{e[2].elapsed_time(e[3]):.2f}" for e in evs), file=sys.stderr,
+              flush=True)
         flops = kept_flops(idx, cnt, N, b)
         kept_frac = float(cnt.to(torch.float64).sum().item()) / (H * cfg.n_blocks * cfg.n_blocks)
         return wall_ms, stage, flops, kept_frac

@@ -542,8 +542,9 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
         }                                                                                                      \
       }                                                                                                        \
     } else {                                                                                                   \
-      o[((S_) >> 1) & 1][BP] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                        \
-          va[UP][((S_) >> 1) & 1][(S_) & 1], __builtin_bit_cast(bf16x8, pw[BP][(S_) & 1]), o[((S_) >> 1) & 1][BP], 0, \
+      /* the two dim blocks alternate: consecutive MFMAs are independent and share the weights  */         \
+      o[(S_) & 1][BP] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                               \
+          va[UP][(S_) & 1][((S_) >> 1) & 1], __builtin_bit_cast(bf16x8, pw[BP][((S_) >> 1) & 1]), o[(S_) & 1][BP], 0, \
           0, 0);                                                                                               \
     }                                                                                                          \
     /* weights, staggered by one slot so that no instruction waits for the one just before it:   */          \
