@@ -6,7 +6,7 @@ HBM: block pooling of Q and K, block scoring + selection, block-sparse attention
 The default workload is the headline shape: 100 frames x 1374 tokens = 137,400 tokens, 16 heads,
 head dim 64, bf16, block 128, tau = 0.9.  The dense kernel is timed on the same inputs.
 
-Prints ONE JSON line (see the design doc for the fields).  `value` is the kept-block throughput of the
+Prints ONE JSON line.  `value` is the kept-block throughput of the
 whole layer: FLOPs of the kept (query block, key block) pairs, counting valid tokens only,
 divided by the layer time.
 """
