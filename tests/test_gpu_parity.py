@@ -292,3 +292,27 @@ def test_determinism(B):
     torch.cuda.synchronize()
     assert torch.equal(a[0], b[0]) and torch.equal(a[1][..., :1], b[1][..., :1]) and torch.equal(a[2], b[2])
     assert torch.equal(a[3], b[3])
+
+
+def test_launch_order_does_not_change_results(B):
+    """With a workspace the sparse kernel launches rows much longer than the mean first; without one
+    in index order.  Every row must come out bitwise the same either way (the order only decides
+    which workgroup computes which row), including empty rows and rows that keep everything."""
+    H, N, b = 8, 160 * 128 - 37, 128
+    q, k, v = _rand_qkv(H, N, 77, "bf16")
+    nb = O.num_blocks(N, b)
+    rng = np.random.default_rng(3)
+    mask = rng.random((H, nb, nb)) < 0.08
+    mask[:, ::17, :] = True            # a few rows keep every block
+    mask[:, 5::31, :] = False          # a few rows keep nothing
+    idx, cnt = _lists(mask)
+    tq, tk, tv = (to_device(x, "bf16") for x in (q, k, v))
+    a = B.bsga_sparse_attn(tq, tk, tv, b, idx, cnt, ordered=True)
+    c = B.bsga_sparse_attn(tq, tk, tv, b, idx, cnt, ordered=False)
+    torch.cuda.synchronize()
+    assert torch.equal(a, c)
+    assert (a[:, 5 * b:6 * b].float() == 0).all()          # an empty row is zeros
+    want = O.sparse_attention(q, k, v, mask, b, q_blocks=[0, 1, 17, nb - 1], heads=[0, 7])
+    want[:, 5 * b:6 * b] = np.nan
+    mx, mean = attn_errors(a, want)
+    assert mx <= _bf16_max_bar(v) and mean <= _bf16_mean_bar(want), (mx, mean)
