@@ -140,7 +140,8 @@ int bsga_select_blocks(const double* q_pool, const double* k_pool, int heads, in
     return fail(BSGA_ERR_INVALID_ARG, "%s: q_pool and k_pool must be 16-byte aligned", fn);
   if (heads < 1 || heads > 65535) return fail(BSGA_ERR_INVALID_ARG, "%s: heads must be in [1, 65535], got %d", fn, heads);
   if (head_dim != 64) return fail(BSGA_ERR_UNSUPPORTED, "%s: head_dim must be 64, got %d", fn, head_dim);
-  if (nb_q < 1) return fail(BSGA_ERR_INVALID_ARG, "%s: nb_q must be >= 1, got %d", fn, nb_q);
+  if (nb_q < 1 || nb_q > (1 << 18))
+    return fail(BSGA_ERR_INVALID_ARG, "%s: nb_q must be in [1, 2^18], got %d", fn, nb_q);
   if (nb_k < 1) return fail(BSGA_ERR_INVALID_ARG, "%s: nb_k must be >= 1, got %d", fn, nb_k);
   if (nb_k > 4096) return fail(BSGA_ERR_UNSUPPORTED, "%s: nb_k above 4096 is not supported, got %d", fn, nb_k);
   if (!isfinite(score_scale)) return fail(BSGA_ERR_INVALID_ARG, "%s: score_scale must be finite", fn);
