@@ -91,7 +91,8 @@ size_t bsga_select_workspace_bytes(int heads, int nb_q, int nb_k);
  *   workspace, workspace_bytes: device scratch of at least bsga_select_workspace_bytes(...) bytes,
  *             16-byte aligned; holds the block logits between the two kernels of this call and is
  *             overwritten; calls sharing one workspace must be stream-ordered.
- * Limits: 1 <= nb_k <= 4096, 1 <= nb_q <= 2^18, heads <= 65535.  score_scale must be finite;
+ * Limits: 1 <= nb_k <= 8192 (rows are held in registers; above 4096 key blocks the kernel spills and
+ * is several times slower per row), 1 <= nb_q <= 2^18, heads <= 65535.  score_scale must be finite;
  * 0 <= tau; 0 <= rho <= 1.
  */
 int bsga_select_blocks(const double* q_pool, const double* k_pool, int heads, int nb_q, int nb_k,

@@ -143,7 +143,7 @@ int bsga_select_blocks(const double* q_pool, const double* k_pool, int heads, in
   if (nb_q < 1 || nb_q > (1 << 18))
     return fail(BSGA_ERR_INVALID_ARG, "%s: nb_q must be in [1, 2^18], got %d", fn, nb_q);
   if (nb_k < 1) return fail(BSGA_ERR_INVALID_ARG, "%s: nb_k must be >= 1, got %d", fn, nb_k);
-  if (nb_k > 4096) return fail(BSGA_ERR_UNSUPPORTED, "%s: nb_k above 4096 is not supported, got %d", fn, nb_k);
+  if (nb_k > 8192) return fail(BSGA_ERR_UNSUPPORTED, "%s: nb_k above 8192 is not supported, got %d", fn, nb_k);
   if (!isfinite(score_scale)) return fail(BSGA_ERR_INVALID_ARG, "%s: score_scale must be finite", fn);
   if (!(tau >= 0.0)) return fail(BSGA_ERR_INVALID_ARG, "%s: tau must be >= 0", fn);
   if (!(rho >= 0.0 && rho <= 1.0)) return fail(BSGA_ERR_INVALID_ARG, "%s: rho must be in [0, 1]", fn);

@@ -153,31 +153,34 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
   // ---- softmax over the ranked blocks: p[r] belongs to block J = 64 r + lane.  Padding (J >= nb_k)
   // and blocks with force_k[J] == 2 (always kept, not ranked) get p = 0 and take no part below.
   double p[E];
-  unsigned long long ranked = 0;  // bit r: block 64 r + lane is ranked
+  unsigned long long ranked[(E + 63) / 64] = {};  // bit r: block 64 r + lane is ranked
   double mx = -INFINITY;
 #pragma unroll
   for (int r = 0; r < E; ++r) {
     const int J = r * 64 + lane;
     bool rk = J < nb_k;
     if (rk && force_k != nullptr) rk = force_k[J] != 2;
-    if (rk) ranked |= 1ull << r;
+    if (rk) ranked[r >> 6] |= 1ull << (r & 63);
     p[r] = rk ? lrow[J] : -INFINITY;
     mx = fmax(mx, p[r]);
   }
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) mx = fmax(mx, __shfl_xor(mx, o));
-  const int nb_ranked = __builtin_amdgcn_readfirstlane(wave_sum_all(static_cast<int>(__popcll(ranked))));
+  int my_ranked = 0;
+#pragma unroll
+  for (int w = 0; w < (E + 63) / 64; ++w) my_ranked += __popcll(ranked[w]);
+  const int nb_ranked = __builtin_amdgcn_readfirstlane(wave_sum_all(my_ranked));
   double z = 0.0;
 #pragma unroll
   for (int r = 0; r < E; ++r) {
-    p[r] = ((ranked >> r) & 1) ? exp(p[r] - mx) : 0.0;
+    p[r] = ((ranked[r >> 6] >> (r & 63)) & 1) ? exp(p[r] - mx) : 0.0;
     z += p[r];
   }
   z = wave_sum_all(z);
   double total = 0.0;
 #pragma unroll
   for (int r = 0; r < E; ++r) {
-    p[r] = ((ranked >> r) & 1) ? p[r] / z : 0.0;
+    p[r] = ((ranked[r >> 6] >> (r & 63)) & 1) ? p[r] / z : 0.0;
     total += p[r];
   }
   total = wave_sum_all(total);
@@ -186,7 +189,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
 #pragma unroll
   for (int r = 0; r < E; ++r) {
     const uint64_t key = static_cast<uint64_t>(__double_as_longlong(p[r]));
-    if ((ranked >> r) & 1) {
+    if ((ranked[r >> 6] >> (r & 63)) & 1) {
       key_min = key < key_min ? key : key_min;
       key_max = key > key_max ? key : key_max;
     }
@@ -238,7 +241,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
       const int J = r * 64 + lane;
       const bool valid = J < nb_k;
       const uint64_t key = static_cast<uint64_t>(__double_as_longlong(p[r]));
-      const bool rk = (ranked >> r) & 1;
+      const bool rk = (ranked[r >> 6] >> (r & 63)) & 1;
       const bool tied = rk && key == T;
       const unsigned long long tb = __ballot(tied);
       const int tie_idx = tie_run + __popcll(tb & below);
@@ -295,7 +298,9 @@ int launch_select(const double* q_pool, const double* k_pool, int heads, int nb_
   BSGA_SELECT_CASE(28)
   BSGA_SELECT_CASE(40)
   BSGA_SELECT_CASE(52)
-  BSGA_SELECT_CASE(64) { return fail(BSGA_ERR_UNSUPPORTED, "bsga_select_blocks: nb_k = %d exceeds 4096", nb_k); }
+  BSGA_SELECT_CASE(64)
+  BSGA_SELECT_CASE(96)
+  BSGA_SELECT_CASE(128) { return fail(BSGA_ERR_UNSUPPORTED, "bsga_select_blocks: nb_k = %d exceeds 8192", nb_k); }
 #undef BSGA_SELECT_CASE
   return check_hip(hipGetLastError(), "bsga_select_blocks launch");
 }

@@ -69,7 +69,7 @@ def test_select_argument_errors(B):
 
     assert call(q=None) == 1
     assert call(nbk=0) == 1 and "nb_k" in _err(B)
-    assert call(nbk=4097, stride=4097) == 2 and "4096" in _err(B)
+    assert call(nbk=8193, stride=8193) == 2 and "8192" in _err(B)
     assert call(d=32) == 2
     assert call(tau=-0.1) == 1 and "tau" in _err(B)
     assert call(tau=float("nan")) == 1

@@ -127,13 +127,14 @@ def test_select_sizes_and_structured_rows(B, nb):
         assert unexcused == 0 and excused == 0, (unexcused, excused)
 
 
-def test_select_max_row_length_and_force(B):
+@pytest.mark.parametrize("nbk", [4096, 6000, 8192])
+def test_select_max_row_length_and_force(B, nbk):
     rng = np.random.default_rng(7)
-    nbq, nbk = 5, 4096
+    nbq = 5
     qp = rng.standard_normal((1, nbq, 64))
     kp = rng.standard_normal((1, nbk, 64))
     fq = np.zeros(nbq, np.uint8); fq[3] = 1
-    fk = np.zeros(nbk, np.uint8); fk[[0, 1, 77, 4095]] = 1
+    fk = np.zeros(nbk, np.uint8); fk[[0, 1, 77, nbk - 1]] = 1
     logits = O.block_logits(qp, kp, 0.125)
     probs = O.block_softmax(logits)
     want = O.select_blocks(probs, 0.6, 1.0, fq, fk)
