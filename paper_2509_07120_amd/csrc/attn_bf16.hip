@@ -236,7 +236,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   const int kh = wave / WQ;
   int h = blockIdx.y, I = blockIdx.x;
   if (order != nullptr) {  // row number blockIdx.y * gridDim.x + blockIdx.x of the launch order
-    const int row = order[int64_t(blockIdx.y) * nb + blockIdx.x];
+    const int row = __builtin_amdgcn_readfirstlane(order[int64_t(blockIdx.y) * nb + blockIdx.x]);
     h = min(max(row / nb, 0), static_cast<int>(gridDim.y) - 1);
     I = min(max(row % nb, 0), nb - 1);
   }
@@ -319,29 +319,31 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   const int32_t* my_idx = dense ? nullptr : kv_idx + rowid * idx_stride;
   const int tail = static_cast<int>(n_tokens - int64_t(nbk - 1) * KB);  // valid keys in the last key block
 
-  // The row's key-block list is read 64 entries at a time, one per lane, and handed out with
-  // readlane; the next 64 are already in flight while the current ones are consumed.
-  int idx_cur = 0, idx_next = 0;
-  auto load_idx = [&](int first) {
-    const int t = first + lane;
-    return (!dense && t < count) ? my_idx[t] : 0;
-  };
-  auto block_at = [&](int it) -> Tile {  // tile number it; must be called with it = 0, 1, 2, ... in order
-    if (dense) return Tile{it, -1};
+  // The row's key-block list is the same for the whole workgroup, so its entries are fetched with
+  // scalar loads (the list is read through a constant-address-space pointer: it is never written
+  // while the kernel runs), which do not count as vector memory operations: the waits on the
+  // direct-to-LDS loads (vmcnt) stay exact.  raw_at(it) only issues the loads of tile `it` (any it;
+  // past the end it repeats the last tile) and hands back the unchecked entries; the caller keeps
+  // them for a tile before fix() turns them into block numbers, so nothing waits for the load.
+  typedef const int32_t __attribute__((address_space(4))) * const_idx_ptr;
+  const const_idx_ptr cidx = (const_idx_ptr)my_idx;
+  auto raw_at = [&](int it) -> Tile {
+    if (dense) return Tile{min(it, nbk - 1), -1};
     constexpr int PER = HALF ? 2 : 1;  // list entries per tile
-    const int e = it * PER;
-    if (it > 0 && (e & 63) == 0) {
-      idx_cur = idx_next;
-      idx_next = load_idx(e + 64);
-    }
-    const int ja = __builtin_amdgcn_readlane(idx_cur, e & 63);
-    Tile t{min(max(ja, 0), nbk - 1), -1};
+    const int e = min(it, ntiles - 1) * PER;
+    Tile t{cidx[e], -1};
+    if constexpr (HALF) t.b = cidx[min(e + 1, count - 1)];
+    return t;
+  };
+  auto fix = [&](const Tile& r, int it) -> Tile {  // r = raw_at(it)
+    if (dense) return r;
+    Tile t{min(max(r.a, 0), nbk - 1), -1};
     if constexpr (HALF) {
-      const int jb = __builtin_amdgcn_readlane(idx_cur, (e + 1) & 63);
-      if (e + 1 < count) t.b = min(max(jb, 0), nbk - 1);
+      if (min(it, ntiles - 1) * 2 + 1 < count) t.b = min(max(r.b, 0), nbk - 1);
     }
     return t;
   };
+  auto block_at = [&](int it) -> Tile { return fix(raw_at(it), it); };
   // valid keys in half `half` of a tile (whole tile if !HALF): the last key block may be ragged
   auto valid_keys = [&](const Tile& t, int half) {
     const int J = (HALF && half == 1) ? t.b : t.a;
@@ -609,6 +611,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
       J_nxt = block_at(1);
       issue(J_nxt, 1);
     }
+    Tile J_pre = raw_at(2);  // fetched one tile before it becomes "the tile after next"
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
     read_k(ka, 0u, 0);
@@ -625,7 +628,8 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     // ---- all tiles but the last --------------------------------------------------------------------
     for (int T = 0; T + 1 < ntiles; ++T) {
       // the tile after next; at the end of the list one more (harmless) load of a valid tile
-      const Tile J2 = (T + 2 < ntiles) ? block_at(T + 2) : J_cur;
+      const Tile J2 = (T + 2 < ntiles) ? fix(J_pre, T + 2) : J_cur;
+      J_pre = raw_at(T + 3);
       tile(std::true_type{}, J_cur, J2, T & 1);
       J_cur = J_nxt;
       J_nxt = J2;
@@ -657,8 +661,6 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
         for (int i = 0; i < 16; ++i) o[db][b2][i] = 0.f;
     m_ref[0] = m_ref[1] = -INFINITY;
     l_run[0] = l_run[1] = 0.f;
-    idx_cur = load_idx(0);
-    idx_next = load_idx(64);
     int pad_keys = 0;  // zero-filled keys past the end that the fast pass has summed as weight 1
     if constexpr (!SAFE && B == 128) fast_loop(pad_keys);
     else plain_loop(safec, pad_keys);

@@ -28,7 +28,7 @@ def _sample_blocks(kept_counts, nb, rng):
     return sorted(picks)
 
 
-@pytest.mark.parametrize("cfg_id,tau,mask_heads,attn_heads", [(3, 0.9, 16, 2), (4, 0.9, 4, 2), (4, 0.8, 2, 1),
+@pytest.mark.parametrize("cfg_id,tau,mask_heads,attn_heads", [(3, 0.9, 16, 2), (4, 0.9, 4, 2), (4, 0.8, 2, 1), (4, 0.95, 2, 1),
                                                              (5, 0.9, 2, 1)])
 def test_full_size_layer(B, cfg_id, tau, mask_heads, attn_heads):
     cfg = CONFIGS[cfg_id]
