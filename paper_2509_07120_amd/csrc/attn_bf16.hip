@@ -430,9 +430,10 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     if (ntiles <= 0) return;
     Tile J_cur = block_at(0);
     issue(J_cur, 0);
+    Tile J_pre = raw_at(1);  // list entries are fetched a tile before they are used
     for (int it = 0; it < ntiles; ++it) {
       const int buf = it & 1;
-      const Tile J_next = (it + 1 < ntiles) ? block_at(it + 1) : Tile{0, -1};
+      const Tile J_next = (it + 1 < ntiles) ? fix(J_pre, it + 1) : Tile{0, -1};
       __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile `it` has landed
       __syncthreads();                     // ... and so has everyone else's; buffer buf^1 is free
       if (it + 1 < ntiles) issue(J_next, buf ^ 1);
@@ -490,6 +491,10 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
             for (int cp = 0; cp < 2; ++cp)
               o[db][b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db][cp], __builtin_bit_cast(bf16x8, w[cp]),
                                                                   o[db][b2], 0, 0, 0);
+          // The list entries of the tile after next.  Scalar loads return out of order with LDS
+          // reads, so a wait for LDS data would also wait for them: they are issued here, where
+          // every LDS read of the tile has been consumed, and used at the top of the next tile.
+          if (u == NH - 1 && b2 == 0) J_pre = raw_at(it + 2);
         }
       }
       J_cur = J_next;
