@@ -81,3 +81,17 @@ def test_topk_only_selection_at_full_size(B):
         _, _, logits, probs, want = oracle_mask_pipeline(q, k, cfg.block, 0.0, rho)
         unexcused, excused = unexcused_mask_mismatches(bits_to_mask(bits, cfg.n_blocks), want, logits, probs, 0.0, rho)
         assert unexcused == 0, (rho, unexcused, excused)
+
+
+def test_keep_all_equals_dense_at_100_frames(B):
+    """A property that needs no oracle run: at the headline size, tau = 1 keeps every block and the
+    block-sparse kernel then walks the same tiles in the same order as the dense kernel, so the two
+    outputs are identical bit for bit (all 16 heads, every row)."""
+    cfg = CONFIGS[4]
+    q, k, v = generate(cfg)
+    tq, tk, tv = (to_device(x, cfg.dtype) for x in (q, k, v))
+    out, kv_idx, kv_cnt, _ = B.sparse_global_attention(tq, tk, tv, cfg.block, 1.0)
+    dense = B.bsga_dense_attn(tq, tk, tv)
+    torch.cuda.synchronize()
+    assert (kv_cnt == cfg.n_blocks).all()
+    assert torch.equal(out, dense)
