@@ -46,14 +46,18 @@ def kept_flops(kv_idx, kv_cnt, n_tokens: int, block: int, block_k: int = 0) -> f
 
 def measured_traffic(cfg_id: int):
     """HBM bytes per launch of the attention kernel, from the committed rocprofv3 --pmc summary
-    (profiles/attention_hbm_traffic.json, written from FETCH_SIZE / WRITE_SIZE runs); None if that
+    (profiles/attention_hbm_traffic.txt, written from FETCH_SIZE / WRITE_SIZE runs); None if that
     workload has not been profiled."""
-    path = os.path.join(ROOT, "profiles", "attention_hbm_traffic.json")
+    path = os.path.join(ROOT, "profiles", "attention_hbm_traffic.txt")
+    key = f"cfg{cfg_id}.hbm_bytes_per_launch"
     try:
         with open(path) as f:
-            return json.load(f).get(f"cfg{cfg_id}", {}).get("hbm_bytes_per_launch")
-    except (OSError, ValueError):
-        return None
+            for line in f:
+                if line.split("=")[0].strip() == key:
+                    return float(line.split("=")[1])
+    except (OSError, ValueError, IndexError):
+        pass
+    return None
 
 
 def cpu_baseline(cfg, tau: float, budget_s: float = 20.0):
