@@ -56,19 +56,32 @@ def num_blocks(n_tokens: int, b: int) -> int:
     return (n_tokens + b - 1) // b
 
 
+def block_ranges(n_tokens: int, b: int, n_first: Optional[int] = None):
+    """Token ranges [lo, hi) of the blocks of size b.  With n_first given, tokens [0, n_first) and
+    [n_first, n_tokens) are cut into blocks separately, so no block holds tokens of both parts
+    (Sec. 4.2: patch tokens and special tokens are kept apart); the last block of each part may be
+    short.  Without it: consecutive blocks, the last one possibly short."""
+    parts = [(0, n_tokens)] if n_first is None else [(0, n_first), (n_first, n_tokens)]
+    out = []
+    for lo, hi in parts:
+        for s in range(lo, hi, b):
+            out.append((s, min(s + b, hi)))
+    return out
+
+
 # --------------------------------------------------------------------------- step 1
-def pool_blocks(x: np.ndarray, b: int) -> np.ndarray:
+def pool_blocks(x: np.ndarray, b: int, n_first: Optional[int] = None) -> np.ndarray:
     """Block average pooling P^b(x) (Sec. 4.1, "Predicting Block Masks").
 
-    x: [H, N, d].  Returns [H, ceil(N/b), d] in fp64.  Block I covers tokens
-    I*b .. min((I+1)*b, N)-1 and is averaged over exactly those tokens.
+    x: [H, N, d].  Returns [H, number of blocks, d] in fp64.  Block I covers tokens
+    I*b .. min((I+1)*b, N)-1 (or, with n_first, the ranges of block_ranges) and is averaged over
+    exactly those tokens.
     """
     x = np.asarray(x, dtype=np.float64)
     H, N, d = x.shape
-    nb = num_blocks(N, b)
-    out = np.empty((H, nb, d), dtype=np.float64)
-    for I in range(nb):
-        lo, hi = I * b, min((I + 1) * b, N)
+    ranges = block_ranges(N, b, n_first)
+    out = np.empty((H, len(ranges), d), dtype=np.float64)
+    for I, (lo, hi) in enumerate(ranges):
         out[:, I, :] = x[:, lo:hi, :].sum(axis=1) / float(hi - lo)
     return out
 
@@ -196,11 +209,13 @@ def sparse_attention(
     heads: Optional[Sequence[int]] = None,
     return_lse: bool = False,
     b_k: Optional[int] = None,
+    n_first: Optional[int] = None,
 ):
     """Eq. (2) with excluded (not zeroed) masked entries.
 
     b is the query block size; key blocks have size b_k (default b), so mask is
-    [H, ceil(N/b), ceil(N/b_k)].
+    [H, ceil(N/b), ceil(N/b_k)].  With n_first the blocks are those of block_ranges(N, ., n_first)
+    (Sec. 4.2: two separately blocked parts) and mask has one row / column per such block.
 
     For token i of query block I the softmax runs over exactly the keys j < N
     that lie in key blocks J with mask[h, I, J] set; o_i is the resulting
@@ -215,18 +230,20 @@ def sparse_attention(
     v = np.asarray(v, dtype=np.float64)
     H, N, d = q.shape
     scale = 1.0 / math.sqrt(d) if softmax_scale is None else softmax_scale
-    nbq = num_blocks(N, b)
     bk = b if b_k is None else b_k
-    assert mask.shape == (H, nbq, num_blocks(N, bk))
+    q_ranges = block_ranges(N, b, n_first)
+    k_ranges = block_ranges(N, bk, n_first)
+    nbq = len(q_ranges)
+    assert mask.shape == (H, nbq, len(k_ranges))
     out = np.full((H, N, d), np.nan, dtype=np.float64)
     lse = np.full((H, N), np.nan, dtype=np.float64)
     head_list = range(H) if heads is None else heads
     block_list = list(range(nbq)) if q_blocks is None else list(q_blocks)
     for h in head_list:
         for I in block_list:
-            rows = slice(I * b, min((I + 1) * b, N))
+            rows = slice(*q_ranges[I])
             kept = np.flatnonzero(mask[h, I])
-            cols = np.concatenate([np.arange(J * bk, min((J + 1) * bk, N)) for J in kept])
+            cols = np.concatenate([np.arange(*k_ranges[J]) for J in kept])
             logits = scale * (q[h, rows] @ k[h, cols].T)
             m = logits.max(axis=1, keepdims=True)
             e = np.exp(logits - m)

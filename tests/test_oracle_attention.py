@@ -179,3 +179,46 @@ def test_asymmetric_blocks_keep_all_is_dense_and_pooling_is_per_side():
         for J in range(5):
             want = s[I * 16:min((I + 1) * 16, N), J * 8:(J + 1) * 8].mean()
             assert abs(logits[0, I, J] - want) < 1e-12
+
+
+# --------------------------------------------------------------------------- two separately blocked parts
+def test_split_blocks_token_level_brute_force():
+    """Sec. 4.2 blocking (tokens [0, n_first) and [n_first, N) cut into blocks separately), also
+    with separate query / key block sizes: every row against a literal masked softmax built from
+    an explicit token -> block map."""
+    rng = np.random.default_rng(13)
+    H, N, d, n_first = 2, 29, 4, 13
+    q, k, v = (rng.standard_normal((H, N, d)) for _ in range(3))
+    for bq, bk in ((4, 4), (8, 4)):
+        def block_of(t, b):  # written out, not taken from the oracle
+            return t // b if t < n_first else -(-n_first // b) + (t - n_first) // b
+        nbq = -(-n_first // bq) + -(-(N - n_first) // bq)
+        nbk = -(-n_first // bk) + -(-(N - n_first) // bk)
+        mask = rng.random((H, nbq, nbk)) < 0.5
+        mask[:, :, 0] = True
+        out, lse = O.sparse_attention(q, k, v, mask, bq, b_k=bk, n_first=n_first, return_lse=True)
+        for h in range(H):
+            allowed = np.array([[mask[h, block_of(i, bq), block_of(j, bk)] for j in range(N)] for i in range(N)])
+            logits = (q[h] @ k[h].T) / np.sqrt(d)
+            logits[~allowed] = -np.inf
+            w = np.exp(logits - logits.max(axis=1, keepdims=True))
+            np.testing.assert_allclose(out[h], (w / w.sum(axis=1, keepdims=True)) @ v[h], rtol=0, atol=1e-12)
+            np.testing.assert_allclose(lse[h], np.log(np.exp(logits).sum(axis=1)), rtol=0, atol=1e-12)
+
+
+def test_split_with_everything_kept_is_dense_and_matches_special_token_statement():
+    rng = np.random.default_rng(14)
+    H, N, d, b, n_first = 1, 37, 8, 8, 27
+    q, k, v = (rng.standard_normal((H, N, d)) for _ in range(3))
+    nb = len(O.block_ranges(N, b, n_first))
+    np.testing.assert_allclose(O.sparse_attention(q, k, v, np.ones((H, nb, nb), bool), b, n_first=n_first),
+                               O.dense_attention(q, k, v), rtol=0, atol=1e-12)
+    # patch tokens first, special tokens last: the split blocking with dense special rows / columns
+    # is the special-token statement of Sec. 4.2
+    patch_idx, special_idx = np.arange(n_first), np.arange(n_first, N)
+    want, pmask = O.special_token_attention(2.0 * q, k, v, patch_idx, special_idx, b, 0.6, 1.0)
+    npb = pmask.shape[-1]
+    mask = np.ones((H, nb, nb), bool)
+    mask[:, :npb, :npb] = pmask
+    assert not pmask.all()
+    np.testing.assert_allclose(O.sparse_attention(2.0 * q, k, v, mask, b, n_first=n_first), want, rtol=0, atol=1e-12)

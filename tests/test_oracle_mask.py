@@ -75,7 +75,7 @@ def test_hand_worked_row():
     s = O.select_row(p, 0.65, 1.0)
     assert list(s.order) == [1, 3, 2, 0]
     assert s.n_cdf == 2 and s.n_keep == 2
-    assert O.select_row(p, 0.7, 1.0).n_keep == 3 - 1 + (0.4 + 0.3 < 0.7)  # boundary decided in fp: 0.4+0.3
+    assert O.select_row(p, 0.69, 1.0).n_keep == 2       # .4 + .3 covers .69 ...
     assert O.select_row(p, 0.71, 1.0).n_keep == 3
     assert O.select_row(p, 0.05, 1.0).n_keep == 1
     assert O.select_row(p, 0.0, 1.0).n_keep == 1        # never an empty row
@@ -192,12 +192,18 @@ def test_index_lists_and_bits_roundtrip():
                 assert bool((bits[h, I, J // 32] >> np.uint32(J % 32)) & np.uint32(1)) == bool(m[h, I, J])
 
 
-def test_predict_mask_matches_manual_chain_on_tiny_case():
-    """Brute force of steps 1-4 with python loops on a tiny ragged case."""
+@pytest.mark.parametrize("scale", [1.0, None])
+def test_predict_mask_matches_manual_chain_on_tiny_case(scale):
+    """Brute force of steps 1-4 with python loops on a tiny ragged case; scale None is the
+    default block-score scale 1/sqrt(d_h) (here 1/sqrt(3), with inputs large enough that the two
+    scales select different blocks)."""
     H, N, d, b = 1, 11, 3, 4
-    q, k = _rand((H, N, d), 20), _rand((H, N, d), 21)
+    q, k = 2.0 * _rand((H, N, d), 20), 2.0 * _rand((H, N, d), 21)
     tau = 0.6
-    m = O.predict_mask(q, k, b, tau, 1.0, score_scale=1.0)
+    m = O.predict_mask(q, k, b, tau, 1.0, score_scale=1.0) if scale is not None else O.predict_mask(q, k, b, tau, 1.0)
+    if scale is None:
+        assert (m != O.predict_mask(q, k, b, tau, 1.0, score_scale=1.0)).any()  # the case tells the scales apart
+    factor = 1.0 if scale is not None else 1.0 / math.sqrt(d)
     nb = 3
     blocks = [range(0, 4), range(4, 8), range(8, 11)]
     for I in range(nb):
@@ -207,7 +213,7 @@ def test_predict_mask_matches_manual_chain_on_tiny_case():
             for i in blocks[I]:
                 for j in blocks[J]:
                     tot += float(np.dot(q[0, i], k[0, j]))
-            s.append(tot / (len(blocks[I]) * len(blocks[J])))
+            s.append(factor * tot / (len(blocks[I]) * len(blocks[J])))
         e = [math.exp(x - max(s)) for x in s]
         p = [x / sum(e) for x in e]
         order = sorted(range(nb), key=lambda j: (-p[j], j))
@@ -217,3 +223,17 @@ def test_predict_mask_matches_manual_chain_on_tiny_case():
             if acc >= tau:
                 break
         assert set(np.flatnonzero(m[0, I]).tolist()) == keep
+
+
+# ---- two separately blocked parts (Sec. 4.2) ----------------------------------------------------
+def test_block_ranges_and_split_pooling():
+    """Blocks never cross n_first; each part ends in its own short block; pooled values are plain
+    means of exactly those tokens."""
+    assert O.block_ranges(11, 4) == [(0, 4), (4, 8), (8, 11)]
+    assert O.block_ranges(11, 4, 6) == [(0, 4), (4, 6), (6, 10), (10, 11)]
+    assert O.block_ranges(11, 4, 11) == O.block_ranges(11, 4) == O.block_ranges(11, 4, 0)
+    assert O.block_ranges(8, 4, 4) == [(0, 4), (4, 8)]
+    x = np.arange(22, dtype=np.float64).reshape(1, 11, 2)
+    p = O.pool_blocks(x, 4, n_first=6)
+    assert p.shape == (1, 4, 2)
+    np.testing.assert_array_equal(p[0, :, 0], [(0 + 2 + 4 + 6) / 4, (8 + 10) / 2, (12 + 14 + 16 + 18) / 4, 20.0])
