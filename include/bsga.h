@@ -61,6 +61,18 @@ int bsga_pool_qk(const void* q, const void* k, int dtype, int heads, int64_t n_t
                  int block, double* q_pool, double* k_pool, void* stream);
 
 /*
+ * Block average pooling when the sequence is split in two parts that are blocked separately
+ * (Sec. 4.2: the patch tokens X_p and the special tokens X_s are kept apart, so that no pooled block
+ * mixes the two kinds).  Tokens [0, n_first) form blocks 0 .. ceil(n_first/block)-1, tokens
+ * [n_first, n_tokens) the blocks after them; the last block of EACH part may be ragged and is
+ * averaged over its own tokens.  nb = ceil(n_first/block) + ceil((n_tokens-n_first)/block).
+ * 0 <= n_first <= n_tokens; n_first = n_tokens (or 0) is bsga_pool_qk.  Otherwise as bsga_pool_qk.
+ */
+int bsga_pool_qk_split(const void* q, const void* k, int dtype, int heads, int64_t n_tokens,
+                       int64_t n_first, int head_dim, int block, double* q_pool, double* k_pool,
+                       void* stream);
+
+/*
  * Bytes of device workspace bsga_select_blocks needs: the float64 block logits
  * [heads, nb_q, nb_k] (Sec. 4.1, the low-resolution score matrix S).  0 for invalid arguments.
  */
@@ -116,7 +128,8 @@ int bsga_gather_tokens(const void* src, int dtype, int heads, int64_t n_src, int
  * Bytes of device workspace bsga_sparse_attn needs for this shape (bsga_dense_attn needs none and
  * accepts NULL).  Q, K and V are read in place and all intermediates stay on chip; the workspace
  * holds the launch order of the (head, query block) rows, heaviest first (4 bytes per row, sized for
- * block 64, plus 128 bytes per head and 16 bytes; 0 for fp32 and for invalid arguments).
+ * block 64 and a split sequence, plus 128 bytes per head and 16 bytes; 0 for fp32 and for invalid
+ * arguments).
  */
 size_t bsga_attn_workspace_bytes(int dtype, int heads, int64_t n_tokens, int head_dim);
 
@@ -155,6 +168,23 @@ int bsga_sparse_attn_qk(const void* q, const void* k, const void* v, int dtype, 
                         int64_t n_tokens, int head_dim, int block_q, int block_k, float softmax_scale,
                         const int32_t* kv_idx, const int32_t* kv_cnt, int idx_stride, void* out,
                         float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Block-sparse attention over a sequence split in two separately blocked parts (Sec. 4.2; Eq. (2) of
+ * Sec. 4.1 on the blocks of bsga_pool_qk_split).  Query block I and key block J are the blocks
+ * described at bsga_pool_qk_split, with block_q tokens per query block and block_k per key block
+ * (the same pairs as bsga_sparse_attn_qk): a block never crosses n_first, and the last block of each
+ * part may be ragged.  kv_idx [heads, nbq, idx_stride], kv_cnt [heads, nbq] with
+ * nbq = ceil(n_first/block_q) + ceil((n_tokens-n_first)/block_q), entries in [0, nbk),
+ * nbk = ceil(n_first/block_k) + ceil((n_tokens-n_first)/block_k), idx_stride >= nbk.
+ * With the patch tokens first and the special tokens after them, every patch token lies in a block
+ * of patch tokens only.  Everything else as bsga_sparse_attn.
+ */
+int bsga_sparse_attn_split(const void* q, const void* k, const void* v, int dtype, int heads,
+                           int64_t n_tokens, int64_t n_first, int head_dim, int block_q, int block_k,
+                           float softmax_scale, const int32_t* kv_idx, const int32_t* kv_cnt,
+                           int idx_stride, void* out, float* lse, void* workspace,
+                           size_t workspace_bytes, void* stream);
 
 /*
  * Dense attention baseline  (Sec. 4.1, Eq. (1)): softmax(softmax_scale * Q K^T) V per head.

@@ -31,12 +31,14 @@ EXPORTED_SYMBOLS = (
     "bsga_version",
     "bsga_last_error",
     "bsga_pool_qk",
+    "bsga_pool_qk_split",
     "bsga_select_workspace_bytes",
     "bsga_select_blocks",
     "bsga_gather_tokens",
     "bsga_attn_workspace_bytes",
     "bsga_sparse_attn",
     "bsga_sparse_attn_qk",
+    "bsga_sparse_attn_split",
     "bsga_dense_attn",
 )
 
@@ -62,6 +64,9 @@ def _load() -> ctypes.CDLL:
     lib.bsga_last_error.argtypes = []
     lib.bsga_pool_qk.restype = c_int
     lib.bsga_pool_qk.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int64, c_int, c_int, c_void_p, c_void_p, c_void_p]
+    lib.bsga_pool_qk_split.restype = c_int
+    lib.bsga_pool_qk_split.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int64, c_int64, c_int, c_int, c_void_p,
+                                       c_void_p, c_void_p]
     lib.bsga_select_blocks.restype = c_int
     lib.bsga_select_blocks.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_double, c_double, c_double,
                                        c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_size_t,
@@ -78,6 +83,10 @@ def _load() -> ctypes.CDLL:
     lib.bsga_sparse_attn_qk.restype = c_int
     lib.bsga_sparse_attn_qk.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int64, c_int, c_int, c_int, c_float,
                                         c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.bsga_sparse_attn_split.restype = c_int
+    lib.bsga_sparse_attn_split.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int64, c_int64, c_int, c_int,
+                                           c_int, c_float, c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_void_p,
+                                           c_size_t, c_void_p]
     lib.bsga_dense_attn.restype = c_int
     lib.bsga_dense_attn.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int64, c_int, c_float,
                                     c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
@@ -131,6 +140,25 @@ def bsga_pool_qk(q: torch.Tensor, k: torch.Tensor, block: int) -> Tuple[torch.Te
     q_pool = torch.empty((H, nb, d), dtype=torch.float64, device=q.device)
     k_pool = torch.empty_like(q_pool)
     _check(lib.bsga_pool_qk(_ptr(q), _ptr(k), _dtype_code(q), H, N, d, block, _ptr(q_pool), _ptr(k_pool), _stream(q)))
+    return q_pool, k_pool
+
+
+def split_blocks(n_tokens: int, n_first: int, block: int) -> int:
+    """Blocks of a sequence whose parts [0, n_first) and [n_first, n_tokens) are blocked separately."""
+    return num_blocks(n_first, block) + num_blocks(n_tokens - n_first, block)
+
+
+def bsga_pool_qk_split(q: torch.Tensor, k: torch.Tensor, block: int, n_first: int) -> Tuple[torch.Tensor, torch.Tensor]:
+    """As bsga_pool_qk for a sequence split at token n_first: no block crosses n_first."""
+    _require(q, "q"); _require(k, "k", q.dtype)
+    if q.shape != k.shape or q.dim() != 3:
+        raise ValueError("q and k must both be [heads, n_tokens, head_dim]")
+    H, N, d = q.shape
+    nb = split_blocks(N, n_first, block) if 0 <= n_first <= N else 1
+    q_pool = torch.empty((H, nb, d), dtype=torch.float64, device=q.device)
+    k_pool = torch.empty_like(q_pool)
+    _check(lib.bsga_pool_qk_split(_ptr(q), _ptr(k), _dtype_code(q), H, N, n_first, d, block, _ptr(q_pool),
+                                  _ptr(k_pool), _stream(q)))
     return q_pool, k_pool
 
 
@@ -217,6 +245,27 @@ def bsga_sparse_attn(q, k, v, block: int, kv_idx: torch.Tensor, kv_cnt: torch.Te
     return (out, lse) if return_lse else out
 
 
+def bsga_sparse_attn_split(q, k, v, block: int, n_first: int, kv_idx: torch.Tensor, kv_cnt: torch.Tensor,
+                           softmax_scale: Optional[float] = None, return_lse: bool = False,
+                           out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                           block_k: Optional[int] = None):
+    """As bsga_sparse_attn for a sequence split at token n_first (blocks as in bsga_pool_qk_split)."""
+    _require(q, "q"); _require(k, "k", q.dtype); _require(v, "v", q.dtype)
+    _require(kv_idx, "kv_idx", torch.int32); _require(kv_cnt, "kv_cnt", torch.int32)
+    H, N, d = q.shape
+    if softmax_scale is None:
+        softmax_scale = 1.0 / math.sqrt(d)
+    if out is None:
+        out = torch.empty_like(q)
+    lse = torch.empty((H, N), dtype=torch.float32, device=q.device) if return_lse else None
+    workspace, ws_bytes = _workspace(q, workspace)
+    _check(lib.bsga_sparse_attn_split(_ptr(q), _ptr(k), _ptr(v), _dtype_code(q), H, N, n_first, d, block,
+                                      block if block_k is None else block_k, float(softmax_scale), _ptr(kv_idx),
+                                      _ptr(kv_cnt), kv_idx.shape[-1], _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes,
+                                      _stream(q)))
+    return (out, lse) if return_lse else out
+
+
 def bsga_dense_attn(q, k, v, softmax_scale: Optional[float] = None, return_lse: bool = False,
                     out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
     """Dense softmax attention baseline; returns O (and lse)."""
@@ -257,11 +306,12 @@ def bsga_gather_tokens(x: torch.Tensor, index: torch.Tensor, out: Optional[torch
 class SpecialTokenPlan:
     """Index bookkeeping for the special-token split (Sec. 4.2), built once per sequence layout.
 
-    The working order puts the patch tokens first (in their original order) and the special tokens
-    last.  The first n_patch_blocks = floor(N_p / block) blocks then hold patch tokens only; they are
-    the blocks the map is predicted on.  Every later block (the N_p mod block left-over patch tokens
-    and all special tokens) is attended and attends densely: force_q = 1, force_k = 2 (kept, not
-    ranked)."""
+    The working order puts the patch tokens X_p first (in their original order) and the special
+    tokens X_s last, and the two parts are blocked separately (the *_split entry points with
+    n_first = N_p): blocks 0 .. n_patch_blocks-1, n_patch_blocks = ceil(N_p / block), hold every patch
+    token and nothing else (the last of them may be ragged); they are the blocks the map is predicted
+    on.  The blocks after them hold the special tokens, which attend and are attended densely:
+    force_q = 1, force_k = 2 (kept, not ranked)."""
 
     def __init__(self, special: torch.Tensor, block: int, device):
         special = torch.as_tensor(special, dtype=torch.bool).cpu()
@@ -272,8 +322,9 @@ class SpecialTokenPlan:
         self.n_tokens = n
         self.block = block
         self.n_patch = int((~special).sum())
-        self.n_patch_blocks = self.n_patch // block
-        nb = num_blocks(n, block)
+        self.n_patch_blocks = num_blocks(self.n_patch, block)
+        nb = split_blocks(n, self.n_patch, block)
+        self.n_blocks = nb
         dense = torch.arange(nb) >= self.n_patch_blocks
         self.perm = order.to(torch.int32).to(device)
         self.inverse = inverse.to(torch.int32).to(device)
@@ -287,8 +338,8 @@ def sparse_global_attention_special(q, k, v, plan: SpecialTokenPlan, tau: float,
     patch blocks only, block-sparse attention, gather back.  Returns (O in the caller's token order,
     kv_idx, kv_cnt, mask_bits); the lists refer to blocks of the working order."""
     qw, kw, vw = (bsga_gather_tokens(x, plan.perm) for x in (q, k, v))
-    q_pool, k_pool = bsga_pool_qk(qw, kw, plan.block)
+    q_pool, k_pool = bsga_pool_qk_split(qw, kw, plan.block, plan.n_patch)
     mask_bits, kv_idx, kv_cnt = bsga_select_blocks(q_pool, k_pool, tau, rho, score_scale, force_q=plan.force_q,
                                                    force_k=plan.force_k)
-    ow = bsga_sparse_attn(qw, kw, vw, plan.block, kv_idx, kv_cnt, softmax_scale)
+    ow = bsga_sparse_attn_split(qw, kw, vw, plan.block, plan.n_patch, kv_idx, kv_cnt, softmax_scale)
     return bsga_gather_tokens(ow, plan.inverse), kv_idx, kv_cnt, mask_bits

@@ -64,12 +64,14 @@ class GlobalAttentionBlock(torch.nn.Module):
         if self.tau >= 1.0 and self.rho >= 1.0:
             o = B.bsga_dense_attn(q, k, v)
         else:
-            q_pool, k_pool = B.bsga_pool_qk(q, k, self.block)
+            # with the split, patch tokens and special tokens are blocked separately (n_first = N_p)
+            n_first = N if self.plan is None else self.plan.n_patch
+            q_pool, k_pool = B.bsga_pool_qk_split(q, k, self.block, n_first)
             fq = None if self.plan is None else self.plan.force_q
             fk = None if self.plan is None else self.plan.force_k
             _, kv_idx, kv_cnt = B.bsga_select_blocks(q_pool, k_pool, self.tau, self.rho, force_q=fq, force_k=fk,
                                                      want_bits=False)
-            o = B.bsga_sparse_attn(q, k, v, self.block, kv_idx, kv_cnt)
+            o = B.bsga_sparse_attn_split(q, k, v, self.block, n_first, kv_idx, kv_cnt)
         self.last = {"q": q, "k": k, "v": v, "o": o}
         y = F.linear(o.permute(1, 0, 2).reshape(N, D), self.w_out, self.b_out)
         if self.plan is not None:

@@ -203,6 +203,14 @@ __global__ __launch_bounds__(256) void order_place_kernel(const int32_t* __restr
   }
 }
 
+// Token blocks.  The sequence is two segments, tokens [0, n_first) and [n_first, n_tokens), each cut
+// into blocks of its own (Sec. 4.2 keeps the patch tokens and the special tokens in separate blocks);
+// nbq1 / nbk1 = number of query / key blocks of the first segment.  n_first = n_tokens is the plain
+// single-segment blocking.
+struct Segments {
+  int n_first, nbq1, nbk1;
+};
+
 // A key tile of B keys in LDS.  With key blocks of B keys it is one listed block (a); with key blocks
 // of B/2 keys it is two consecutive entries of the row's list, one per half (b < 0: the list ended,
 // the second half is empty).
@@ -217,7 +225,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     const unsigned char* __restrict__ q, const unsigned char* __restrict__ k, const unsigned char* __restrict__ v,
     unsigned short* __restrict__ out, float* __restrict__ lse, const int32_t* __restrict__ kv_idx,
     const int32_t* __restrict__ kv_cnt, const int32_t* __restrict__ order, int idx_stride, int64_t n_tokens, int nb,
-    int nbk, float scale_log2) {
+    int nbk, float scale_log2, Segments seg) {
   static_assert(KB == B || (2 * KB == B && B == 128), "key blocks are whole tiles or half tiles of 128");
   constexpr bool HALF = KB != B;          // two listed key blocks per tile
   constexpr int WQ = B / 64;              // waves along queries (64 rows each)
@@ -243,6 +251,10 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   }
   const int64_t head_bytes = int64_t(h) * n_tokens * 128;
   const int64_t rowid = int64_t(h) * nb + I;
+  // this query block: first token and number of tokens (a block never crosses the segment boundary)
+  const int n_tok = static_cast<int>(n_tokens);
+  const int q_start = I < seg.nbq1 ? I * B : seg.n_first + (I - seg.nbq1) * B;
+  const int q_valid = min(B, (I < seg.nbq1 ? seg.n_first : n_tok) - q_start);
   // raw buffer views of this head's K and V (byte-addressed, bounds-checked by the hardware)
   const unsigned head_size = static_cast<unsigned>(n_tokens * 128);
   const i32x4 krsrc = make_rsrc(k + head_bytes, head_size);
@@ -255,7 +267,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   bf16x8 qf[2][4];
 #pragma unroll
   for (int b2 = 0; b2 < 2; ++b2) {
-    const int64_t row = int64_t(I) * B + qi * 64 + b2 * 32 + n;
+    const int64_t row = int64_t(q_start) + qi * 64 + b2 * 32 + n;  // rows past q_valid are computed, not stored
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       u32x4 x = {0u, 0u, 0u, 0u};
@@ -318,7 +330,10 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   const int count = dense ? nbk : min(max(kv_cnt[rowid], 0), nbk);  // listed key blocks
   const int ntiles = HALF ? (count + 1) >> 1 : count;
   const int32_t* my_idx = dense ? nullptr : kv_idx + rowid * idx_stride;
-  const int tail = static_cast<int>(n_tokens - int64_t(nbk - 1) * KB);  // valid keys in the last key block
+  // key block J: first token and number of tokens.  Blocks of the first segment (J < nbk1) tile
+  // tokens [0, n_first), the others tokens [n_first, n_tokens); the last block of each may be ragged.
+  auto key_start = [&](int J) { return J < seg.nbk1 ? J * KB : seg.n_first + (J - seg.nbk1) * KB; };
+  auto key_count = [&](int J) { return min(KB, (J < seg.nbk1 ? seg.n_first : n_tok) - key_start(J)); };
 
   // The row's key-block list is the same for the whole workgroup, so its entries are fetched with
   // scalar loads (the list is read through a constant-address-space pointer: it is never written
@@ -345,18 +360,40 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     return t;
   };
   auto block_at = [&](int it) -> Tile { return fix(raw_at(it), it); };
-  // valid keys in half `half` of a tile (whole tile if !HALF): the last key block may be ragged
-  auto valid_keys = [&](const Tile& t, int half) {
-    const int J = (HALF && half == 1) ? t.b : t.a;
-    if (J < 0) return 0;
-    return (J == nbk - 1) ? tail : KB;
+  // This wave's keys of a tile are the tile rows [kh*KW, (kh+1)*KW).  wave_limit(t) is the first of
+  // them that is not a key of the listed block (a ragged block, or an absent second half): rows at
+  // or past it hold zeros or tokens of another block, and their scores are masked before they are
+  // exponentiated.  A full tile gives (kh+1)*KW.
+  auto wave_limit = [&](const Tile& t) {
+    const int J = (HALF && kh == 1) ? t.b : t.a;
+    const int cnt = J < 0 ? 0 : key_count(J);
+    return HALF ? kh * KW + cnt : min(cnt, (kh + 1) * KW);
   };
-  auto padded_keys = [&](const Tile& t) {  // keys of the tile that do not exist (zero-filled in LDS)
-    return HALF ? (2 * KB - valid_keys(t, 0) - valid_keys(t, 1)) : (B - valid_keys(t, 0));
+  // scores of the wave's 32-key sub-tile u: keys at or past `limit` (tile row numbers) get weight 0
+  // (register i of the lane is tile row kh*KW + 32u + 8(i/4) + 4g + i%4).  Runs for the few ragged
+  // tiles only; the lane number is taken afresh through an opaque instruction, so that nothing of
+  // this is computed ahead and kept in registers across the tile loops.
+  auto mask_keys = [&](f32x16& sc, int u, int limit) {
+    int l;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+    const int t = limit - kh * KW - u * 32 - ((l >> 5) << 2);  // row 8(i/4) + i%4 is masked iff it is >= t
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sc[i] = (8 * (i >> 2) + (i & 3) >= t) ? -INFINITY : sc[i];
+  };
+  // Does the tile hold rows that are not keys of its listed block(s)?  The same answer in every wave
+  // of the workgroup (the pipelined loop below leaves such tiles to the plain tile code, and all
+  // waves must agree on that).  Only the last block of each segment can be short.
+  const int short_a = (seg.n_first % KB) != 0 ? seg.nbk1 - 1 : -1;
+  const int short_b = ((n_tok - seg.n_first) % KB) != 0 ? nbk - 1 : -1;
+  auto tile_ragged = [&](const Tile& t) {
+    bool r = t.a == short_a || t.a == short_b;
+    if constexpr (HALF) r = r || t.b < 0 || t.b == short_a || t.b == short_b;
+    return r;
   };
   // Direct-to-LDS load number i2 (0..7) of key tile J into buffer pair `buf`: even i2 moves 1 KB of
-  // the K tile, odd i2 1 KB of the V tile.  Rows of a ragged last tile that lie past the end of the
-  // head's buffer fail the hardware bounds check, which makes the load write zeros for them.
+  // the K tile, odd i2 1 KB of the V tile.  Rows that lie past the end of the head's buffer fail
+  // the hardware bounds check, which makes the load write zeros for them (so V rows past the end
+  // are finite; rows past a ragged block inside the sequence hold the following tokens).
   // With half-tile key blocks, loads i = 0, 1 fill tile rows 0..63 from block a and i = 2, 3 rows
   // 64..127 from block b; an absent b gets an offset past the end of the buffer, so the bounds check
   // zero-fills that half.
@@ -366,14 +403,14 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     const unsigned dst = smem_addr + wave * 1024 + NW * i * 1024 + (is_v ? V_BASE : 0) + buf * TILE_BYTES;
     if constexpr (HALF) {
       const int Jx = (i >> 1) ? J.b : J.a;
-      const unsigned soff = Jx < 0 ? head_size : static_cast<unsigned>(Jx) * (KB * 128);
+      const unsigned soff = Jx < 0 ? head_size : static_cast<unsigned>(key_start(Jx)) * 128u;
       if (is_v) {
         dma16(vrsrc, voff, soff + (Jx < 0 ? 0u : (i & 1) * NW * 1024), dst);
       } else {
         dma16(krsrc, koff[i % KN], soff, dst);
       }
     } else {
-      const unsigned soff = static_cast<unsigned>(J.a) * TILE_BYTES;
+      const unsigned soff = static_cast<unsigned>(key_start(J.a)) * 128u;
       if (is_v) {
         dma16(vrsrc, voff, soff + i * NW * 1024, dst);
       } else {
@@ -418,92 +455,90 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   };
 
   // ---------------------------------------------------------------------------------------------
-  // Plain tile loop: per (32-key sub-tile, query half) scores (4 MFMAs) -> weights -> O update
-  // (4 MFMAs), one barrier per tile, the next tile's loads in flight meanwhile.  Used for the SAFE
-  // pass and for block 64.
+  // One tile, plain form: per (32-key sub-tile, query half) scores (4 MFMAs) -> weights -> O update
+  // (4 MFMAs), from the tile buffers at byte offset boff.  `limit` = wave_limit of the tile.
   //   SAFE = true: online softmax.  The accumulator of the score MFMA starts at -m_ref, so the MFMA
   //   result is already relative to the reference, and m_ref is raised only when a sub-tile exceeds
-  //   it by more than 2^kRaise.  Keys of the ragged last tile that lie past the end are masked.
-  //   SAFE = false: reference 0, no maximum, no masking: the zero-filled keys past the end each add
-  //   exactly 2^0 = 1 to the row sum and nothing to O; pass() subtracts their count.
-  auto plain_loop = [&](auto safec, int& pad_keys) {
+  //   it by more than 2^kRaise.
+  //   SAFE = false: reference 0, no maximum.
+  // In both forms the scores of tile rows that are not keys of the listed block are masked.
+  // after_reads() runs once every LDS read of the tile has been consumed.
+  // ka, va, sc, w: working registers (the pipelined loop lends its own, which are free between runs).
+  auto compute_tile = [&](auto safec, unsigned boff, int limit, auto&& after_reads, bf16x8 (&ka)[4],
+                          bf16x8 (&va)[2][2], f32x16& sc, u32x4 (&w)[2]) {
     constexpr bool SAFE = decltype(safec)::value;
+    const bool ragged = limit < (kh + 1) * KW;
+#pragma unroll
+    for (int u = 0; u < NH; ++u) {
+      read_k(ka, boff, u);
+      read_v(va, boff, u);
+#pragma unroll
+      for (int b2 = 0; b2 < 2; ++b2) {
+        const float base = (SAFE && m_ref[b2] != -INFINITY) ? m_ref[b2] : 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sc[i] = -base;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c], qf[b2][c], sc, 0, 0, 0);
+        if (ragged) mask_keys(sc, u, limit);
+        if constexpr (SAFE) {
+          float tmax = -INFINITY;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sc[i]);
+          tmax = fmaxf(tmax, xor32(tmax));
+          const bool unset = m_ref[b2] == -INFINITY;
+          const bool raise = unset ? (tmax > -INFINITY) : (tmax > kRaise);
+          if (__any(raise)) {  // rare after the first tile
+            const float shift = raise ? tmax : 0.f;
+            const float alpha = unset ? 1.f : exp2f(-shift);  // nothing accumulated yet while unset
+            if (raise) m_ref[b2] = base + shift;
+            l_run[b2] *= alpha;
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+              for (int i = 0; i < 16; ++i) o[db][b2][i] *= alpha;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sc[i] -= shift;
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) weigh_pair(sc, w, l_run[b2], j);
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+          for (int cp = 0; cp < 2; ++cp)
+            o[db][b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db][cp], __builtin_bit_cast(bf16x8, w[cp]),
+                                                                o[db][b2], 0, 0, 0);
+        if (u == NH - 1 && b2 == 0) after_reads();
+      }
+    }
+  };
+
+  // Plain tile loop: compute_tile per tile, one barrier per tile, the next tile's loads in flight
+  // meanwhile.  Used for the SAFE pass and for block 64.
+  auto plain_loop = [&](auto safec) {
     if (ntiles <= 0) return;
     Tile J_cur = block_at(0);
     issue(J_cur, 0);
     Tile J_pre = raw_at(1);  // list entries are fetched a tile before they are used
+    bf16x8 ka[4], va[2][2];
+    f32x16 sc;
+    u32x4 w[2];
     for (int it = 0; it < ntiles; ++it) {
       const int buf = it & 1;
       const Tile J_next = (it + 1 < ntiles) ? fix(J_pre, it + 1) : Tile{0, -1};
       __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile `it` has landed
       __syncthreads();                     // ... and so has everyone else's; buffer buf^1 is free
       if (it + 1 < ntiles) issue(J_next, buf ^ 1);
-      const unsigned boff = buf * TILE_BYTES;
-      const bool ragged = padded_keys(J_cur) > 0;
-      if (ragged && !SAFE) pad_keys += padded_keys(J_cur);
-      // first key of the tile (counted from the tile's start) that this wave must mask in SAFE mode
-      const int limit = HALF ? kh * KW + valid_keys(J_cur, kh) : valid_keys(J_cur, 0);
-#pragma unroll
-      for (int u = 0; u < NH; ++u) {
-        bf16x8 ka[4], va[2][2];
-        read_k(ka, boff, u);
-        read_v(va, boff, u);
-#pragma unroll
-        for (int b2 = 0; b2 < 2; ++b2) {
-          const float base = (SAFE && m_ref[b2] != -INFINITY) ? m_ref[b2] : 0.f;
-          f32x16 sc;
-#pragma unroll
-          for (int i = 0; i < 16; ++i) sc[i] = -base;
-#pragma unroll
-          for (int c = 0; c < 4; ++c) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c], qf[b2][c], sc, 0, 0, 0);
-          if constexpr (SAFE) {
-            if (ragged) {
-#pragma unroll
-              for (int i = 0; i < 16; ++i) {
-                const int key = kh * KW + u * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-                if (key >= limit) sc[i] = -INFINITY;
-              }
-            }
-            float tmax = -INFINITY;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sc[i]);
-            tmax = fmaxf(tmax, xor32(tmax));
-            const bool unset = m_ref[b2] == -INFINITY;
-            const bool raise = unset ? (tmax > -INFINITY) : (tmax > kRaise);
-            if (__any(raise)) {  // rare after the first tile
-              const float shift = raise ? tmax : 0.f;
-              const float alpha = unset ? 1.f : exp2f(-shift);  // nothing accumulated yet while unset
-              if (raise) m_ref[b2] = base + shift;
-              l_run[b2] *= alpha;
-#pragma unroll
-              for (int db = 0; db < 2; ++db)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) o[db][b2][i] *= alpha;
-#pragma unroll
-              for (int i = 0; i < 16; ++i) sc[i] -= shift;
-            }
-          }
-          u32x4 w[2];
-#pragma unroll
-          for (int j = 0; j < 8; ++j) weigh_pair(sc, w, l_run[b2], j);
-#pragma unroll
-          for (int db = 0; db < 2; ++db)
-#pragma unroll
-            for (int cp = 0; cp < 2; ++cp)
-              o[db][b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db][cp], __builtin_bit_cast(bf16x8, w[cp]),
-                                                                  o[db][b2], 0, 0, 0);
-          // The list entries of the tile after next.  Scalar loads return out of order with LDS
-          // reads, so a wait for LDS data would also wait for them: they are issued here, where
-          // every LDS read of the tile has been consumed, and used at the top of the next tile.
-          if (u == NH - 1 && b2 == 0) J_pre = raw_at(it + 2);
-        }
-      }
+      // The list entries of the tile after next.  Scalar loads return out of order with LDS reads, so
+      // a wait for LDS data would also wait for them: they are issued where every LDS read of the
+      // tile has been consumed, and used at the top of the next tile.
+      compute_tile(safec, buf * TILE_BYTES, wave_limit(J_cur), [&]() { J_pre = raw_at(it + 2); }, ka, va, sc, w);
       J_cur = J_next;
     }
   };
 
   // ---------------------------------------------------------------------------------------------
-  // Fast pass for block 128: the same arithmetic as plain_loop<SAFE = false>, software pipelined
+  // Fast pass for block 128: the same arithmetic as compute_tile<SAFE = false>, software pipelined
   // inside the wave.  A unit is (32-key sub-tile u, query half b): scores QK (4 MFMAs into 16
   // registers), weights W (16 exp2, 8 packs, 16 adds), O update PV (4 MFMAs).  A tile has four units
   // n = 0..3 = (u0,b0), (u0,b1), (u1,b0), (u1,b1).  While the VALU works on W(n) the matrix pipe gets
@@ -514,40 +549,38 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   // synchronises once: the next tile is known to have landed (its first K operands are read right
   // after the last score MFMA of this tile) and the current buffers are free, so the eight loads of
   // the tile after next are issued into them, one after each of the following MFMAs.
-  auto fast_loop = [&](int& pad_keys) {
+  //
+  // The pipelined code has no masking in it (a conditional in the slot sequence costs 5 %): it runs
+  // over the row's leading full tiles.  From the first tile with rows that are not keys (a short
+  // block, an absent half) the remaining tiles go through compute_tile, which masks.  With ascending
+  // lists that is the row's last tile, or, for a split sequence with the short first segment's
+  // blocks listed last but a few, the last few tiles.  Either way a tile costs every wave exactly
+  // one barrier, and the loads stay two tiles ahead.
+  auto fast_loop = [&]() {
     if (ntiles <= 0) return;
     f32x16 sc[2];        // scores: [query half]
     u32x4 pw[2][2];      // weights as packed bf16 pairs: [query half][16-key chunk]
     bf16x8 ka[4];        // K operands of the sub-tile whose scores are computed next
     bf16x8 va[2][2][2];  // V^T operands: [sub-tile][dim block][16-key chunk]
     float ex[2][2];      // exponentiated scores of the key pair that is packed in the next slot
-#pragma unroll
-    for (int cp = 0; cp < 2; ++cp) {
-      pw[1][cp] = u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-      for (int db = 0; db < 2; ++db) va[1][db][cp] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
-    }
 
-    // one unit N = (sub-tile N/2, query half N%2).  Slots 0..3: MFMA of QK(N+1) (if do_qk) + one
-    // weight pair; slots 4..7: MFMA of PV(N-1) + one weight pair.  mid(slot) places LDS reads, the
-    // barrier and loads after that slot's MFMA.
-    auto unit = [&](auto nc, auto doqkc, auto&& mid) {
+    // one unit N = (sub-tile N/2, query half N%2).  Slots 0..3: MFMA of QK(N+1) + one weight pair;
+    // slots 4..7: MFMA of PV(N-1) + one weight pair.  mid(slot) places LDS reads, the barrier and
+    // loads after that slot's MFMA.
+    auto unit = [&](auto nc, auto&& mid) {
       constexpr int N = decltype(nc)::value;
       constexpr int BQ = N & 1;                 // query half whose weights are computed
       constexpr int BN = (N + 1) & 1;           // query half of QK(N+1)
       constexpr int BP = (N + 3) & 1;           // query half of PV(N-1)
       constexpr int UP = ((N + 3) & 3) >> 1;    // sub-tile of PV(N-1)
-      constexpr bool do_qk = decltype(doqkc)::value;
 #define BSGA_SLOT(S_)                                                                                          \
   {                                                                                                            \
     if constexpr ((S_) < 4) {                                                                                  \
-      if constexpr (do_qk) {                                                                                   \
-        if constexpr ((S_) == 0) {                                                                             \
-          const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}; \
-          sc[BN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qf[BN][0], zero, 0, 0, 0);                   \
-        } else {                                                                                               \
-          sc[BN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[(S_) & 3], qf[BN][(S_) & 3], sc[BN], 0, 0, 0);    \
-        }                                                                                                      \
+      if constexpr ((S_) == 0) {                                                                               \
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   \
+        sc[BN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qf[BN][0], zero, 0, 0, 0);                     \
+      } else {                                                                                                 \
+        sc[BN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[(S_) & 3], qf[BN][(S_) & 3], sc[BN], 0, 0, 0);      \
       }                                                                                                        \
     } else {                                                                                                   \
       /* the two dim blocks alternate: consecutive MFMAs are independent and share the weights  */         \
@@ -578,38 +611,38 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
 #undef BSGA_SLOT
     };
 
-    // a whole tile in buffer pair `buf` (byte offset boff; the other pair is at boff ^ TILE_BYTES).
+    // a whole (full) tile in buffer pair `buf` (byte offset boff; the other pair is at boff ^ TILE_BYTES).
     // On entry: sc[0] = QK(0) of this tile, ka = K operands of sub-tile 0, pw[1] / va[1] = weights /
-    // V operands of the previous tile's unit 3 (zeros before the first tile).
-    auto tile = [&](auto hasnextc, const Tile& J, const Tile& J_next2, int buf) {
-      constexpr bool has_next = decltype(hasnextc)::value;
-      pad_keys += padded_keys(J);
+    // V operands of the previous tile's unit 3 (zeros at the start of a run).  What it prepares for
+    // the following tile (K operands and first scores from the other buffer) goes unused when the run
+    // ends here.
+    auto tile = [&](const Tile& J_next2, int buf) {
       const unsigned boff = buf * TILE_BYTES;
-      unit(Int<0>{}, std::true_type{}, [&](auto slot) {  // QK(1); K(u1); PV(previous 3); V(u0)
+      unit(Int<0>{}, [&](auto slot) {  // QK(1); K(u1); PV(previous 3); V(u0)
         constexpr int S = decltype(slot)::value;
         if constexpr (S == 0) read_v(va[0], boff, 0);
         if constexpr (S == 3) read_k(ka, boff, 1);
       });
-      unit(Int<1>{}, std::true_type{}, [&](auto slot) {  // QK(2); PV(0); V(u1)
+      unit(Int<1>{}, [&](auto slot) {  // QK(2); PV(0); V(u1)
         constexpr int S = decltype(slot)::value;
         if constexpr (S == 0) read_v(va[1], boff, 1);
       });
-      unit(Int<2>{}, std::true_type{}, [&](auto slot) {  // synchronise; QK(3); K(next tile u0); PV(1) + loads 0..3
+      unit(Int<2>{}, [&](auto slot) {  // synchronise; QK(3); K(next tile u0); PV(1) + loads 0..3
         constexpr int S = decltype(slot)::value;
         if constexpr (S == 0) {
           __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of the next tile has landed
           __syncthreads();                     // every read of this tile is complete in every wave
         }
-        if constexpr (S == 3 && has_next) read_k(ka, boff ^ TILE_BYTES, 0);
+        if constexpr (S == 3) read_k(ka, boff ^ TILE_BYTES, 0);
         if constexpr (S >= 4) issue_part(J_next2, buf, S - 4);
       });
-      unit(Int<3>{}, hasnextc, [&](auto slot) {  // QK(next tile's unit 0); PV(2) + loads 4..7
+      unit(Int<3>{}, [&](auto slot) {  // QK(next tile's unit 0); PV(2) + loads 4..7
         constexpr int S = decltype(slot)::value;
         if constexpr (S >= 4) issue_part(J_next2, buf, S);
       });
     };
 
-    // ---- prologue: tiles 0 and 1 on their way, K operands of sub-tile 0, QK(0) ----------------------
+    // ---- tiles 0 and 1 on their way ----------------------------------------------------------------
     Tile J_cur = block_at(0);
     issue(J_cur, 0);
     Tile J_nxt = J_cur;
@@ -620,34 +653,57 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     Tile J_pre = raw_at(2);  // fetched one tile before it becomes "the tile after next"
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
-    read_k(ka, 0u, 0);
-    {
-      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qf[0][0], zero, 0, 0, 0);
+    // Invariant at the top of the loop: tile T lies in buffer T&1 and every wave knows it; the loads
+    // of tile T+1 into the other buffer have been issued; J_cur / J_nxt are tiles T / T+1 and J_pre
+    // holds the raw list entries of tile T+2.
+    int T = 0;
+    if (!tile_ragged(J_cur)) {
+      // ---- the run of full tiles: K operands of sub-tile 0, QK(0), nothing pending for the O update --
+      read_k(ka, 0u, 0);
 #pragma unroll
-      for (int c = 1; c < 4; ++c) sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c], qf[0][c], sc[0], 0, 0, 0);
+      for (int cp = 0; cp < 2; ++cp) {
+        pw[1][cp] = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int db = 0; db < 2; ++db) va[1][db][cp] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
+      }
+      {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0], qf[0][0], zero, 0, 0, 0);
+#pragma unroll
+        for (int c = 1; c < 4; ++c) sc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c], qf[0][c], sc[0], 0, 0, 0);
+      }
+      ex[0][0] = __builtin_amdgcn_exp2f(sc[0][0]);
+      ex[0][1] = __builtin_amdgcn_exp2f(sc[0][1]);
+      __builtin_amdgcn_sched_barrier(0);
+      do {
+        // the tile after next; at the end of the list one more (harmless) load of a valid tile
+        const Tile J2 = (T + 2 < ntiles) ? fix(J_pre, T + 2) : J_cur;
+        J_pre = raw_at(T + 3);
+        tile(J2, T & 1);
+        J_cur = J_nxt;
+        J_nxt = J2;
+        ++T;
+      } while (T < ntiles && !tile_ragged(J_cur));
+      // ---- the O update of the run's last unit --------------------------------------------------------
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int cp = 0; cp < 2; ++cp)
+          o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[1][db][cp], __builtin_bit_cast(bf16x8, pw[1][cp]),
+                                                             o[db][1], 0, 0, 0);
     }
-    ex[0][0] = __builtin_amdgcn_exp2f(sc[0][0]);
-    ex[0][1] = __builtin_amdgcn_exp2f(sc[0][1]);
-    __builtin_amdgcn_sched_barrier(0);
-
-    // ---- all tiles but the last --------------------------------------------------------------------
-    for (int T = 0; T + 1 < ntiles; ++T) {
-      // the tile after next; at the end of the list one more (harmless) load of a valid tile
+    // ---- from the first ragged tile on: plain tiles (the same buffers and the same one barrier per
+    // tile; the loads stay two tiles ahead) ------------------------------------------------------------
+    for (; T < ntiles; ++T) {
+      compute_tile(std::false_type{}, (T & 1) * TILE_BYTES, wave_limit(J_cur), []() {}, ka, va[0], sc[0], pw[0]);
       const Tile J2 = (T + 2 < ntiles) ? fix(J_pre, T + 2) : J_cur;
       J_pre = raw_at(T + 3);
-      tile(std::true_type{}, J_cur, J2, T & 1);
+      __builtin_amdgcn_s_waitcnt(0x0F70);  // this wave's share of tile T+1 has landed
+      __syncthreads();                     // ... everyone's has, and nobody still reads tile T
+      issue(J2, T & 1);
       J_cur = J_nxt;
       J_nxt = J2;
     }
-    // ---- the last tile, then the O update of its last unit -----------------------------------------
-    tile(std::false_type{}, J_cur, J_cur, (ntiles - 1) & 1);
-#pragma unroll
-    for (int db = 0; db < 2; ++db)
-#pragma unroll
-      for (int cp = 0; cp < 2; ++cp)
-        o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[1][db][cp], __builtin_bit_cast(bf16x8, pw[1][cp]),
-                                                           o[db][1], 0, 0, 0);
   };
 
   // A whole pass over the row's key tiles, then the merge of the two key halves (wave (qi, 1) parks
@@ -667,9 +723,8 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
         for (int i = 0; i < 16; ++i) o[db][b2][i] = 0.f;
     m_ref[0] = m_ref[1] = -INFINITY;
     l_run[0] = l_run[1] = 0.f;
-    int pad_keys = 0;  // zero-filled keys past the end that the fast pass has summed as weight 1
-    if constexpr (!SAFE && B == 128) fast_loop(pad_keys);
-    else plain_loop(safec, pad_keys);
+    if constexpr (!SAFE && B == 128) fast_loop();
+    else plain_loop(safec);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // no direct-to-LDS load may still be in flight
     __syncthreads();                     // ... in any wave: LDS can be reused
 
@@ -708,10 +763,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
         }
         float l = l_run[b2] * a0 + l1 * a1;
         l += xor32(l);
-        if constexpr (!SAFE) {
-          l -= static_cast<float>(pad_keys);
-          bad = bad || !(l >= 0x1p-80f && l <= 0x1p100f);
-        }
+        if constexpr (!SAFE) bad = bad || !(l >= 0x1p-80f && l <= 0x1p100f);
         lt[b2] = l;
 #pragma unroll
         for (int db = 0; db < 2; ++db)
@@ -734,8 +786,9 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
 #pragma unroll
       for (int b2 = 0; b2 < 2; ++b2) {
         const float inv = lt[b2] > 0.f ? 1.f / lt[b2] : 0.f;
-        const int64_t row = int64_t(I) * B + qi * 64 + b2 * 32 + n;
-        if (row < n_tokens) {
+        const int lrow = qi * 64 + b2 * 32 + n;
+        const int64_t row = int64_t(q_start) + lrow;
+        if (lrow < q_valid) {
 #pragma unroll
           for (int db = 0; db < 2; ++db)
 #pragma unroll
@@ -760,11 +813,13 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
 
 }  // namespace
 
-int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int64_t n_tokens, int block,
-                     int block_k, float softmax_scale, const int32_t* kv_idx, const int32_t* kv_cnt, int idx_stride,
-                     void* out, float* lse, void* workspace, hipStream_t stream) {
-  const int nb = static_cast<int>(ceil_div(n_tokens, block));     // query blocks
-  const int nbk = static_cast<int>(ceil_div(n_tokens, block_k));  // key blocks the lists refer to
+int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int64_t n_tokens, int64_t n_first,
+                     int block, int block_k, float softmax_scale, const int32_t* kv_idx, const int32_t* kv_cnt,
+                     int idx_stride, void* out, float* lse, void* workspace, hipStream_t stream) {
+  const int nb = static_cast<int>(split_blocks(n_tokens, n_first, block));     // query blocks
+  const int nbk = static_cast<int>(split_blocks(n_tokens, n_first, block_k));  // key blocks the lists refer to
+  const Segments seg = {static_cast<int>(n_first), static_cast<int>(ceil_div(n_first, block)),
+                        static_cast<int>(ceil_div(n_first, block_k))};
   const int32_t* order = nullptr;
   // ordering matters only when the grid does not fit the chip at once
   if (kv_idx != nullptr && workspace != nullptr && int64_t(heads) * nb >= 1024 && int64_t(heads) * nb < (int64_t(1) << 30)) {
@@ -795,13 +850,13 @@ int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int
   }
   if (block == 64) {
     hipLaunchKernelGGL((attn_bf16_kernel<64, 64>), grid, dim3(128), lds64, stream, qp, kp, vp, op, lse, kv_idx,
-                       kv_cnt, order, idx_stride, n_tokens, nb, nbk, scale_log2);
+                       kv_cnt, order, idx_stride, n_tokens, nb, nbk, scale_log2, seg);
   } else if (block_k == 128) {
     hipLaunchKernelGGL((attn_bf16_kernel<128, 128>), grid, dim3(256), lds128, stream, qp, kp, vp, op, lse, kv_idx,
-                       kv_cnt, order, idx_stride, n_tokens, nb, nbk, scale_log2);
+                       kv_cnt, order, idx_stride, n_tokens, nb, nbk, scale_log2, seg);
   } else {
     hipLaunchKernelGGL((attn_bf16_kernel<128, 64>), grid, dim3(256), lds128, stream, qp, kp, vp, op, lse, kv_idx,
-                       kv_cnt, order, idx_stride, n_tokens, nb, nbk, scale_log2);
+                       kv_cnt, order, idx_stride, n_tokens, nb, nbk, scale_log2, seg);
   }
   return check_hip(hipGetLastError(), "bsga bf16 attention launch");
 }

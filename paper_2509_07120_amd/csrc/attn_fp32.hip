@@ -13,7 +13,8 @@ constexpr int kD = 64;
 
 template <int B>
 __global__ __launch_bounds__(B) void attn_fp32_kernel(const float* __restrict__ q, const float* __restrict__ k,
-                                                      const float* __restrict__ v, int64_t n_tokens, int nb,
+                                                      const float* __restrict__ v, int64_t n_tokens,
+                                                      int64_t n_first, int nb1, int nb,
                                                       float scale_log2, const int32_t* __restrict__ kv_idx,
                                                       const int32_t* __restrict__ kv_cnt, int idx_stride,
                                                       float* __restrict__ out, float* __restrict__ lse) {
@@ -23,8 +24,13 @@ __global__ __launch_bounds__(B) void attn_fp32_kernel(const float* __restrict__ 
   const int h = blockIdx.y;
   const int t = threadIdx.x;
   const int64_t head_off = int64_t(h) * n_tokens * kD;
-  const int64_t qi = int64_t(I) * B + t;
-  const bool qvalid = qi < n_tokens;
+  // blocks 0 .. nb1-1 tile tokens [0, n_first), the others tokens [n_first, n_tokens)
+  auto block_start = [&](int J) { return J < nb1 ? int64_t(J) * B : n_first + int64_t(J - nb1) * B; };
+  auto block_count = [&](int J) {
+    return static_cast<int>(min<int64_t>(B, (J < nb1 ? n_first : n_tokens) - block_start(J)));
+  };
+  const int64_t qi = block_start(I) + t;
+  const bool qvalid = t < block_count(I);
 
   float qr[kD], o[kD];
 #pragma unroll
@@ -42,8 +48,8 @@ __global__ __launch_bounds__(B) void attn_fp32_kernel(const float* __restrict__ 
   for (int it = 0; it < count; ++it) {
     int J = dense ? it : kv_idx[row * idx_stride + it];
     J = min(max(J, 0), nb - 1);
-    const int64_t key0 = int64_t(J) * B;
-    const int valid = static_cast<int>(min<int64_t>(B, n_tokens - key0));
+    const int64_t key0 = block_start(J);
+    const int valid = block_count(J);
     __syncthreads();
     for (int c = t; c < B * (kD / 4); c += B) {
       const int r = c / (kD / 4), d4 = c % (kD / 4);
@@ -86,17 +92,18 @@ __global__ __launch_bounds__(B) void attn_fp32_kernel(const float* __restrict__ 
 
 }  // namespace
 
-int launch_attn_fp32(const float* q, const float* k, const float* v, int heads, int64_t n_tokens, int block,
-                     float softmax_scale, const int32_t* kv_idx, const int32_t* kv_cnt, int idx_stride, float* out,
+int launch_attn_fp32(const float* q, const float* k, const float* v, int heads, int64_t n_tokens, int64_t n_first,
+                     int block, float softmax_scale, const int32_t* kv_idx, const int32_t* kv_cnt, int idx_stride, float* out,
                      float* lse, hipStream_t stream) {
-  const int nb = static_cast<int>(ceil_div(n_tokens, block));
+  const int nb = static_cast<int>(split_blocks(n_tokens, n_first, block));
+  const int nb1 = static_cast<int>(ceil_div(n_first, block));
   const float scale_log2 = softmax_scale * 1.4426950408889634f;
   dim3 grid(nb, heads);
   if (block == 64)
-    hipLaunchKernelGGL((attn_fp32_kernel<64>), grid, dim3(64), 0, stream, q, k, v, n_tokens, nb, scale_log2, kv_idx,
+    hipLaunchKernelGGL((attn_fp32_kernel<64>), grid, dim3(64), 0, stream, q, k, v, n_tokens, n_first, nb1, nb, scale_log2, kv_idx,
                        kv_cnt, idx_stride, out, lse);
   else
-    hipLaunchKernelGGL((attn_fp32_kernel<128>), grid, dim3(128), 0, stream, q, k, v, n_tokens, nb, scale_log2,
+    hipLaunchKernelGGL((attn_fp32_kernel<128>), grid, dim3(128), 0, stream, q, k, v, n_tokens, n_first, nb1, nb, scale_log2,
                        kv_idx, kv_cnt, idx_stride, out, lse);
   return check_hip(hipGetLastError(), "bsga fp32 attention launch");
 }

@@ -48,19 +48,21 @@ static int check_block(const char* fn, int block) {
 static size_t attn_workspace(int dtype, int heads, int64_t n_tokens) {
   // Q, K and V are read in place and every intermediate stays on chip; the only scratch is the
   // launch order of the (head, query block) rows of the sparse bf16 kernel: one int32 per row, sized
-  // for the smaller block size, plus a [32 classes][heads] table.
+  // for the smaller block size (plus one block for a split sequence), plus a [32 classes][heads] table.
   if (dtype != BSGA_BF16) return 0;
-  return (static_cast<size_t>(heads) * static_cast<size_t>(ceil_div(n_tokens, 64)) + 32u * static_cast<size_t>(heads) + 4u) *
+  return (static_cast<size_t>(heads) * static_cast<size_t>(ceil_div(n_tokens, 64) + 1) + 32u * static_cast<size_t>(heads) + 4u) *
          sizeof(int32_t);
 }
 
 static int attn_common(const char* fn, const void* q, const void* k, const void* v, int dtype, int heads,
-                       int64_t n_tokens, int head_dim, int block, int block_k, float softmax_scale,
+                       int64_t n_tokens, int64_t n_first, int head_dim, int block, int block_k, float softmax_scale,
                        const int32_t* kv_idx, const int32_t* kv_cnt, int idx_stride, void* out, float* lse,
                        void* workspace, size_t workspace_bytes, void* stream) {
   clear_error();
   if (int rc = check_shape(fn, dtype, heads, n_tokens, head_dim)) return rc;
   if (int rc = check_block(fn, block)) return rc;
+  if (n_first < 0 || n_first > n_tokens)
+    return fail(BSGA_ERR_INVALID_ARG, "%s: n_first must be in [0, n_tokens], got %lld", fn, (long long)n_first);
   if (block_k != block) {
     if (!(block == 128 && block_k == 64))
       return fail(BSGA_ERR_UNSUPPORTED, "%s: key blocks must have the query block size, or 64 with query blocks of 128 (got %d / %d)",
@@ -73,7 +75,7 @@ static int attn_common(const char* fn, const void* q, const void* k, const void*
     return fail(BSGA_ERR_INVALID_ARG, "%s: q, k, v and out must be 16-byte aligned", fn);
   if (!(softmax_scale > 0.0f) || !isfinite(softmax_scale))
     return fail(BSGA_ERR_INVALID_ARG, "%s: softmax_scale must be finite and > 0", fn);
-  const int64_t nb = ceil_div(n_tokens, block_k);
+  const int64_t nb = split_blocks(n_tokens, n_first, block_k);
   if (kv_idx || kv_cnt) {
     if (!kv_idx || !kv_cnt) return fail(BSGA_ERR_INVALID_ARG, "%s: kv_idx and kv_cnt must both be given", fn);
     if (idx_stride < nb)
@@ -88,10 +90,10 @@ static int attn_common(const char* fn, const void* q, const void* k, const void*
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (dtype == BSGA_BF16)
-    return launch_attn_bf16(q, k, v, heads, n_tokens, block, block_k, softmax_scale, kv_idx, kv_cnt, idx_stride, out, lse,
+    return launch_attn_bf16(q, k, v, heads, n_tokens, n_first, block, block_k, softmax_scale, kv_idx, kv_cnt, idx_stride, out, lse,
                             workspace, s);
   return launch_attn_fp32(static_cast<const float*>(q), static_cast<const float*>(k), static_cast<const float*>(v),
-                          heads, n_tokens, block, softmax_scale, kv_idx, kv_cnt, idx_stride,
+                          heads, n_tokens, n_first, block, softmax_scale, kv_idx, kv_cnt, idx_stride,
                           static_cast<float*>(out), lse, s);
 }
 
@@ -101,16 +103,17 @@ using namespace bsga;
 
 extern "C" {
 
-int bsga_version(void) { return 2; }
+int bsga_version(void) { return 3; }
 
 const char* bsga_last_error(void) { return g_err; }
 
-int bsga_pool_qk(const void* q, const void* k, int dtype, int heads, int64_t n_tokens, int head_dim, int block,
-                 double* q_pool, double* k_pool, void* stream) {
-  const char* fn = "bsga_pool_qk";
+static int pool_common(const char* fn, const void* q, const void* k, int dtype, int heads, int64_t n_tokens,
+                       int64_t n_first, int head_dim, int block, double* q_pool, double* k_pool, void* stream) {
   clear_error();
   if (int rc = check_shape(fn, dtype, heads, n_tokens, head_dim)) return rc;
   if (int rc = check_block(fn, block)) return rc;
+  if (n_first < 0 || n_first > n_tokens)
+    return fail(BSGA_ERR_INVALID_ARG, "%s: n_first must be in [0, n_tokens], got %lld", fn, (long long)n_first);
   if ((q == nullptr) != (q_pool == nullptr) || (k == nullptr) != (k_pool == nullptr))
     return fail(BSGA_ERR_INVALID_ARG, "%s: each input must come with its output (q with q_pool, k with k_pool)", fn);
   if (!q && !k) return fail(BSGA_ERR_INVALID_ARG, "%s: nothing to pool (q and k are both null)", fn);
@@ -118,10 +121,21 @@ int bsga_pool_qk(const void* q, const void* k, int dtype, int heads, int64_t n_t
     return fail(BSGA_ERR_INVALID_ARG, "%s: pointers must be 16-byte aligned", fn);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (q)
-    if (int rc = launch_pool(q, dtype, heads, n_tokens, block, q_pool, s)) return rc;
+    if (int rc = launch_pool(q, dtype, heads, n_tokens, n_first, block, q_pool, s)) return rc;
   if (k)
-    if (int rc = launch_pool(k, dtype, heads, n_tokens, block, k_pool, s)) return rc;
+    if (int rc = launch_pool(k, dtype, heads, n_tokens, n_first, block, k_pool, s)) return rc;
   return BSGA_OK;
+}
+
+int bsga_pool_qk(const void* q, const void* k, int dtype, int heads, int64_t n_tokens, int head_dim, int block,
+                 double* q_pool, double* k_pool, void* stream) {
+  return pool_common("bsga_pool_qk", q, k, dtype, heads, n_tokens, n_tokens, head_dim, block, q_pool, k_pool, stream);
+}
+
+int bsga_pool_qk_split(const void* q, const void* k, int dtype, int heads, int64_t n_tokens, int64_t n_first,
+                       int head_dim, int block, double* q_pool, double* k_pool, void* stream) {
+  return pool_common("bsga_pool_qk_split", q, k, dtype, heads, n_tokens, n_first, head_dim, block, q_pool, k_pool,
+                     stream);
 }
 
 size_t bsga_select_workspace_bytes(int heads, int nb_q, int nb_k) {
@@ -188,7 +202,7 @@ int bsga_sparse_attn(const void* q, const void* k, const void* v, int dtype, int
     clear_error();
     return fail(BSGA_ERR_INVALID_ARG, "bsga_sparse_attn: kv_idx and kv_cnt must be non-null");
   }
-  return attn_common("bsga_sparse_attn", q, k, v, dtype, heads, n_tokens, head_dim, block, block, softmax_scale,
+  return attn_common("bsga_sparse_attn", q, k, v, dtype, heads, n_tokens, n_tokens, head_dim, block, block, softmax_scale,
                      kv_idx, kv_cnt, idx_stride, out, lse, workspace, workspace_bytes, stream);
 }
 
@@ -200,7 +214,19 @@ int bsga_sparse_attn_qk(const void* q, const void* k, const void* v, int dtype, 
     clear_error();
     return fail(BSGA_ERR_INVALID_ARG, "bsga_sparse_attn_qk: kv_idx and kv_cnt must be non-null");
   }
-  return attn_common("bsga_sparse_attn_qk", q, k, v, dtype, heads, n_tokens, head_dim, block_q, block_k,
+  return attn_common("bsga_sparse_attn_qk", q, k, v, dtype, heads, n_tokens, n_tokens, head_dim, block_q, block_k,
+                     softmax_scale, kv_idx, kv_cnt, idx_stride, out, lse, workspace, workspace_bytes, stream);
+}
+
+int bsga_sparse_attn_split(const void* q, const void* k, const void* v, int dtype, int heads, int64_t n_tokens,
+                           int64_t n_first, int head_dim, int block_q, int block_k, float softmax_scale,
+                           const int32_t* kv_idx, const int32_t* kv_cnt, int idx_stride, void* out, float* lse,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  if (!kv_idx || !kv_cnt) {
+    clear_error();
+    return fail(BSGA_ERR_INVALID_ARG, "bsga_sparse_attn_split: kv_idx and kv_cnt must be non-null");
+  }
+  return attn_common("bsga_sparse_attn_split", q, k, v, dtype, heads, n_tokens, n_first, head_dim, block_q, block_k,
                      softmax_scale, kv_idx, kv_cnt, idx_stride, out, lse, workspace, workspace_bytes, stream);
 }
 
@@ -208,7 +234,7 @@ int bsga_dense_attn(const void* q, const void* k, const void* v, int dtype, int 
                     int head_dim, float softmax_scale, void* out, float* lse, void* workspace,
                     size_t workspace_bytes, void* stream) {
   const int block = (dtype == BSGA_FP32) ? 64 : 128;
-  return attn_common("bsga_dense_attn", q, k, v, dtype, heads, n_tokens, head_dim, block, block, softmax_scale, nullptr,
+  return attn_common("bsga_dense_attn", q, k, v, dtype, heads, n_tokens, n_tokens, head_dim, block, block, softmax_scale, nullptr,
                      nullptr, 0, out, lse, workspace, workspace_bytes, stream);
 }
 

@@ -18,8 +18,14 @@ int check_hip(hipError_t e, const char* what);
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// Number of blocks when tokens [0, n_first) and [n_first, n_tokens) are cut into blocks separately
+// (no block crosses n_first).  n_first = n_tokens or 0 gives ceil(n_tokens / block).
+inline int64_t split_blocks(int64_t n_tokens, int64_t n_first, int64_t block) {
+  return ceil_div(n_first, block) + ceil_div(n_tokens - n_first, block);
+}
+
 // Kernel launchers.  Arguments are already validated.
-int launch_pool(const void* x, int dtype, int heads, int64_t n_tokens, int block, double* pooled,
+int launch_pool(const void* x, int dtype, int heads, int64_t n_tokens, int64_t n_first, int block, double* pooled,
                 hipStream_t stream);
 
 int launch_select(const double* q_pool, const double* k_pool, int heads, int nb_q, int nb_k,
@@ -31,11 +37,11 @@ size_t select_workspace_bytes(int heads, int nb_q, int nb_k);
 int launch_gather(const void* src, int dtype, int heads, int64_t n_src, const int32_t* index,
                   int64_t n_dst, void* dst, hipStream_t stream);
 
-int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int64_t n_tokens,
+int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int64_t n_tokens, int64_t n_first,
                      int block, int block_k, float softmax_scale, const int32_t* kv_idx, const int32_t* kv_cnt,
                      int idx_stride, void* out, float* lse, void* workspace, hipStream_t stream);
 
-int launch_attn_fp32(const float* q, const float* k, const float* v, int heads, int64_t n_tokens,
+int launch_attn_fp32(const float* q, const float* k, const float* v, int heads, int64_t n_tokens, int64_t n_first,
                      int block, float softmax_scale, const int32_t* kv_idx, const int32_t* kv_cnt,
                      int idx_stride, float* out, float* lse, hipStream_t stream);
 

@@ -32,7 +32,7 @@ __device__ inline void widen4(const uint4& raw, double* acc) {
 // ELEM_BYTES: 2 = bf16, 4 = fp32.
 template <int ELEM_BYTES, int B>
 __global__ __launch_bounds__(kThreads) void pool_kernel(const uint4* __restrict__ x, double* __restrict__ pooled,
-                                                        int64_t n_tokens, int nb) {
+                                                        int64_t n_tokens, int64_t n_first, int nb1, int nb) {
   constexpr int E = 16 / ELEM_BYTES;     // elements per 16-byte chunk
   constexpr int CH = kD / E;             // chunks per token row
   constexpr int TL = kThreads / CH;      // tokens covered per pass
@@ -44,8 +44,9 @@ __global__ __launch_bounds__(kThreads) void pool_kernel(const uint4* __restrict_
   const int t = threadIdx.x;
   const int cg = t % CH;
   const int tl = t / CH;
-  const int64_t tok0 = int64_t(I) * B;
-  const int valid = static_cast<int>(min<int64_t>(B, n_tokens - tok0));
+  // blocks 0 .. nb1-1 tile tokens [0, n_first), the others tokens [n_first, n_tokens)
+  const int64_t tok0 = I < nb1 ? int64_t(I) * B : n_first + int64_t(I - nb1) * B;
+  const int valid = static_cast<int>(min<int64_t>(B, (I < nb1 ? n_first : n_tokens) - tok0));
   const uint4* base = x + (int64_t(h) * n_tokens + tok0) * CH;
 
   double acc[E];
@@ -76,17 +77,18 @@ __global__ __launch_bounds__(kThreads) void pool_kernel(const uint4* __restrict_
 
 }  // namespace
 
-int launch_pool(const void* x, int dtype, int heads, int64_t n_tokens, int block, double* pooled,
+int launch_pool(const void* x, int dtype, int heads, int64_t n_tokens, int64_t n_first, int block, double* pooled,
                 hipStream_t stream) {
-  const int nb = static_cast<int>(ceil_div(n_tokens, block));
+  const int nb = static_cast<int>(split_blocks(n_tokens, n_first, block));
+  const int nb1 = static_cast<int>(ceil_div(n_first, block));
   dim3 grid(nb, heads), blk(kThreads);
   const uint4* xp = static_cast<const uint4*>(x);
   if (dtype == BSGA_BF16) {
-    if (block == 64) hipLaunchKernelGGL((pool_kernel<2, 64>), grid, blk, 0, stream, xp, pooled, n_tokens, nb);
-    else hipLaunchKernelGGL((pool_kernel<2, 128>), grid, blk, 0, stream, xp, pooled, n_tokens, nb);
+    if (block == 64) hipLaunchKernelGGL((pool_kernel<2, 64>), grid, blk, 0, stream, xp, pooled, n_tokens, n_first, nb1, nb);
+    else hipLaunchKernelGGL((pool_kernel<2, 128>), grid, blk, 0, stream, xp, pooled, n_tokens, n_first, nb1, nb);
   } else {
-    if (block == 64) hipLaunchKernelGGL((pool_kernel<4, 64>), grid, blk, 0, stream, xp, pooled, n_tokens, nb);
-    else hipLaunchKernelGGL((pool_kernel<4, 128>), grid, blk, 0, stream, xp, pooled, n_tokens, nb);
+    if (block == 64) hipLaunchKernelGGL((pool_kernel<4, 64>), grid, blk, 0, stream, xp, pooled, n_tokens, n_first, nb1, nb);
+    else hipLaunchKernelGGL((pool_kernel<4, 128>), grid, blk, 0, stream, xp, pooled, n_tokens, n_first, nb1, nb);
   }
   return check_hip(hipGetLastError(), "bsga_pool_qk launch");
 }

@@ -208,8 +208,9 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
   // k = floor(B (1 - rho)) in binary64 as the definition is written, B = number of ranked blocks
   const int k_floor = static_cast<int>(floor(static_cast<double>(nb_ranked) * one_minus_rho));
   const int k_target = min(nb_ranked, max(k_floor, 1));
-  // tau >= 1, or the mass never gets there (also: nothing is ranked)
-  const bool keep_all = !(total >= tau) || nb_ranked == 0;
+  // tau >= 1 keeps every block by definition (the summed mass may round to 1.0 before blocks of
+  // negligible mass are counted); so does a mass that never gets to tau, and a row with nothing ranked
+  const bool keep_all = tau >= 1.0 || !(total >= tau) || nb_ranked == 0;
   uint64_t T = 0;
   int n_ties = 0;
   if (!keep_all) {

@@ -28,7 +28,7 @@ def test_header_symbols_are_exported(B):
     raw = ctypes.CDLL(B.LIB_PATH)
     for n in names:
         assert hasattr(raw, n), n
-    assert B.lib.bsga_version() == 2
+    assert B.lib.bsga_version() == 3
 
 
 def test_header_compiles_as_plain_c(tmp_path):
@@ -112,10 +112,24 @@ def test_attention_argument_errors(B):
 def test_workspace_size(B):
     """Attention keeps every intermediate on chip; the sparse bf16 kernel wants 4 bytes per query block."""
     import torch
-    assert B.bsga_attn_workspace_bytes(torch.bfloat16, 16, 137400) == (16 * 2147 + 32 * 16 + 4) * 4
+    assert B.bsga_attn_workspace_bytes(torch.bfloat16, 16, 137400) == (16 * (2147 + 1) + 32 * 16 + 4) * 4  # one spare block for a split sequence
     assert B.bsga_attn_workspace_bytes(torch.float32, 16, 137400) == 0
     # selection keeps the float64 block logits between its two kernels
     assert B.bsga_select_workspace_bytes(16, 1074, 1074) == 16 * 1074 * 1074 * 8
     assert B.bsga_select_workspace_bytes(0, 10, 10) == 0
     assert B.bsga_attn_workspace_bytes(torch.float32, 16, 2748) == 0
     assert B.lib.bsga_attn_workspace_bytes(0, 0, 100, 64) == 0
+
+
+def test_split_argument_errors(B):
+    L = B.lib
+    assert L.bsga_pool_qk_split(A, A, 0, 16, 100, 101, 64, 64, A, A, None) == 1 and "n_first" in _err(B)
+    assert L.bsga_pool_qk_split(A, A, 0, 16, 100, -1, 64, 64, A, A, None) == 1 and "n_first" in _err(B)
+    args = (A, A, A, 0, 16, 1000)
+    assert L.bsga_sparse_attn_split(*args, 1001, 64, 128, 128, 0.125, A, A, 16, A, None, None, 0, None) == 1
+    assert "n_first" in _err(B)
+    # 1000 tokens split at 130: key blocks of 128 -> 2 + 7 = 9 blocks, so a stride of 8 is too short
+    assert L.bsga_sparse_attn_split(*args, 130, 64, 128, 128, 0.125, A, A, 8, A, None, None, 0, None) == 1
+    assert "idx_stride" in _err(B)
+    assert L.bsga_sparse_attn_split(*args, 130, 64, 64, 128, 0.125, A, A, 16, A, None, None, 0, None) == 2
+    assert L.bsga_sparse_attn_split(*args, 130, 64, 128, 128, 0.125, None, A, 16, A, None, None, 0, None) == 1

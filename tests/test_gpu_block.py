@@ -48,9 +48,9 @@ def test_block_against_fp64_chain(B, use_special, tau, rho):
     # 1. attention on the block's own q, k, v (working order) against the oracle
     if use_special:
         n_patch = int((~special).sum())
-        npb = n_patch // b
-        patch_idx = np.arange(npb * b)                    # working order: patch tokens first
-        special_idx = np.arange(npb * b, N)
+        npb = -(-n_patch // b)                            # the last patch block is ragged
+        patch_idx = np.arange(n_patch)                    # working order: every patch token first,
+        special_idx = np.arange(n_patch, N)               # then every special token
         if tau >= 1.0:
             want = O.dense_attention(q, k, v)
         else:

@@ -22,15 +22,16 @@ def B():
     return pkg
 
 
-def _sample_blocks(kept_counts, nb, rng):
+def _sample_blocks(kept_counts, nb, rng, n_blocks):
     picks = {0, nb - 1, int(np.argmin(kept_counts)), int(np.argmax(kept_counts))}
-    picks.update(int(x) for x in rng.integers(0, nb, 2))
+    while len(picks) < n_blocks:
+        picks.add(int(rng.integers(0, nb)))
     return sorted(picks)
 
 
-@pytest.mark.parametrize("cfg_id,tau,mask_heads,attn_heads", [(3, 0.9, 16, 2), (4, 0.9, 4, 2), (4, 0.8, 2, 1), (4, 0.95, 2, 1),
-                                                             (5, 0.9, 2, 1)])
-def test_full_size_layer(B, cfg_id, tau, mask_heads, attn_heads):
+@pytest.mark.parametrize("cfg_id,tau,mask_heads,attn_heads,n_blocks", [(3, 0.9, 16, 4, 8), (4, 0.9, 4, 4, 8), (4, 0.8, 2, 2, 6),
+                                                                      (4, 0.95, 2, 2, 6), (5, 0.9, 2, 4, 8)])
+def test_full_size_layer(B, cfg_id, tau, mask_heads, attn_heads, n_blocks):
     cfg = CONFIGS[cfg_id]
     q, k, v = generate(cfg)
     tq, tk, tv = (to_device(x, cfg.dtype) for x in (q, k, v))
@@ -53,8 +54,8 @@ def test_full_size_layer(B, cfg_id, tau, mask_heads, attn_heads):
     # attention: sampled units, sparse against the oracle on the GPU's own mask, dense against Eq. (1)
     rng = np.random.default_rng(cfg_id)
     worst = [0.0, 0.0, 0.0, 0.0]
-    for h in range(attn_heads):
-        blocks = _sample_blocks(cnt[h], nb, rng)
+    for h in [(5 * i) % cfg.heads for i in range(attn_heads)]:   # heads 0, 5, 10, 15
+        blocks = _sample_blocks(cnt[h], nb, rng, n_blocks)
         qh, kh_, vh = q[h:h + 1], k[h:h + 1], v[h:h + 1]
         want = O.sparse_attention(qh, kh_, vh, got_mask[h:h + 1], cfg.block, q_blocks=blocks)
         mx, mean = attn_errors(out[h:h + 1], want)

@@ -13,30 +13,13 @@ import torch
 
 from oracle import bsga_oracle as O
 from workload import CONFIGS, generate
-from tests.helpers import (attn_errors, bits_to_mask, lists_to_mask, oracle_mask_pipeline, to_device,
+from tests.helpers import (attn_errors, bf16_bars_ok, bits_to_mask, lists_to_mask, oracle_mask_pipeline, to_device,
                            unexcused_mask_mismatches)
 
 pytestmark = pytest.mark.gpu
 
 BF16_MAX, BF16_MEAN = 1e-2, 1e-3
 FP32_MAX, FP32_MEAN = 1e-5, 1e-6
-
-
-def _bf16_max_bar(v):
-    """Max-abs bar for the random small-shape cases.  The softmax weights that multiply V are
-    rounded to bf16 (relative error <= 2^-9 each, and the row sum is taken over the rounded
-    weights), so |o_hat - o| <= 2 * 2^-9 * max|v|, plus 2^-9 |o| <= 2^-9 max|v| for rounding the
-    output itself.  The benchmark shapes have max|v| * attention spread small enough for the flat
-    1e-2 bar; a few sharply attended unit-normal values of magnitude 3-4 do not."""
-    return max(BF16_MAX, 1.5 * float(np.abs(v).max()) / 256.0)
-
-
-def _bf16_mean_bar(want):
-    """Mean-abs bar for the random small-shape cases.  With a handful of unit-normal keys the
-    outputs are O(1) instead of the O(0.1) of the benchmark shapes, and rounding the output
-    alone to bf16 costs up to 2^-9 |o| per element; the bar therefore never drops below
-    2^-8 * mean|o| (output rounding plus the equally sized rounding of the softmax weights)."""
-    return max(BF16_MEAN, float(np.nanmean(np.abs(want))) / 256.0)
 
 
 @pytest.fixture(scope="module")
@@ -127,6 +110,31 @@ def test_select_sizes_and_structured_rows(B, nb):
         assert unexcused == 0 and excused == 0, (unexcused, excused)
 
 
+def test_select_tau_one_keeps_blocks_of_negligible_mass(B):
+    """tau >= 1 keeps every block by definition (Sec. 4.1, "Selecting Blocks"; tau = 1 must equal
+    dense attention): also blocks whose probability is below the rounding of the row's total, here a
+    logit spread of 80 .. 200 nats (p down to e^-200)."""
+    rng = np.random.default_rng(5)
+    nb = 70
+    qp = rng.standard_normal((2, nb, 64)) * 6.0
+    kp = rng.standard_normal((2, nb, 64)) * 6.0
+    logits = O.block_logits(qp, kp, 0.125)
+    assert (logits.max(-1) - logits.min(-1)).min() > 60.0
+    want = O.select_blocks(O.block_softmax(logits), 1.0, 1.0)
+    assert want.all()
+    bits, idx, cnt = B.bsga_select_blocks(torch.from_numpy(qp).cuda(), torch.from_numpy(kp).cuda(), 1.0, 1.0)
+    torch.cuda.synchronize()
+    assert bits_to_mask(bits, nb).all() and (cnt.cpu().numpy() == nb).all()
+    # just below 1 the rule is the ranked prefix again, bit-exact with the oracle
+    tau = 1.0 - 2.0 ** -40
+    probs = O.block_softmax(logits)
+    want = O.select_blocks(probs, tau, 1.0)
+    bits, idx, cnt = B.bsga_select_blocks(torch.from_numpy(qp).cuda(), torch.from_numpy(kp).cuda(), tau, 1.0)
+    torch.cuda.synchronize()
+    unexcused, excused = unexcused_mask_mismatches(bits_to_mask(bits, nb), want, logits, probs, tau, 1.0)
+    assert unexcused == 0 and not want.all()
+
+
 @pytest.mark.parametrize("nbk", [4096, 6000, 8192])
 def test_select_max_row_length_and_force(B, nbk):
     rng = np.random.default_rng(7)
@@ -176,9 +184,11 @@ def test_sparse_attention_small_shapes(B, dtype, b, N):
                                   return_lse=True)
     torch.cuda.synchronize()
     want, want_lse = O.sparse_attention(q, k, v, mask, b, return_lse=True)
-    mx, mean = attn_errors(out, want)
-    lim = (_bf16_max_bar(v), _bf16_mean_bar(want)) if dtype == "bf16" else (FP32_MAX, FP32_MEAN)
-    assert mx <= lim[0] and mean <= lim[1], (mx, mean)
+    if dtype == "bf16":
+        assert bf16_bars_ok(out, want)[0], bf16_bars_ok(out, want)
+    else:
+        mx, mean = attn_errors(out, want)
+        assert mx <= FP32_MAX and mean <= FP32_MEAN, (mx, mean)
     assert np.abs(lse.cpu().numpy() - want_lse).max() <= (2e-2 if dtype == "bf16" else 1e-5)
 
 
@@ -189,9 +199,11 @@ def test_dense_attention_small_shapes(B, dtype, N):
     out, lse = B.bsga_dense_attn(to_device(q, dtype), to_device(k, dtype), to_device(v, dtype), return_lse=True)
     torch.cuda.synchronize()
     want, want_lse = O.dense_attention(q, k, v, return_lse=True)
-    mx, mean = attn_errors(out, want)
-    lim = (_bf16_max_bar(v), _bf16_mean_bar(want)) if dtype == "bf16" else (FP32_MAX, FP32_MEAN)
-    assert mx <= lim[0] and mean <= lim[1], (mx, mean)
+    if dtype == "bf16":
+        assert bf16_bars_ok(out, want)[0], bf16_bars_ok(out, want)
+    else:
+        mx, mean = attn_errors(out, want)
+        assert mx <= FP32_MAX and mean <= FP32_MEAN, (mx, mean)
     assert np.abs(lse.cpu().numpy() - want_lse).max() <= (2e-2 if dtype == "bf16" else 1e-5)
 
 
@@ -315,5 +327,4 @@ def test_launch_order_does_not_change_results(B):
     assert (a[:, 5 * b:6 * b].float() == 0).all()          # an empty row is zeros
     want = O.sparse_attention(q, k, v, mask, b, q_blocks=[0, 1, 17, nb - 1], heads=[0, 7])
     want[:, 5 * b:6 * b] = np.nan
-    mx, mean = attn_errors(a, want)
-    assert mx <= _bf16_max_bar(v) and mean <= _bf16_mean_bar(want), (mx, mean)
+    assert bf16_bars_ok(a, want)[0], bf16_bars_ok(a, want)

@@ -80,25 +80,25 @@ def test_all_columns_unranked_keeps_everything(B):
 
 
 def _run_layer(B, cfg, heads, frames, tau, rho, patch_blocks):
+    """The layer with the split against the oracle's statement of Sec. 4.2: X_p = every patch token,
+    X_s = every special token (the oracle gets the paper's two sets, not a layout of the kernels)."""
     q, k, v = generate(cfg, heads=heads, frames=frames)
     N = q.shape[1]
     special = _special_flags(frames, cfg.tokens_per_frame)
     b = cfg.block
-    n_patch = int((~special).sum())
-    npb = n_patch // b
-    # the oracle's sets: X_p = the first npb*b patch tokens, X_s = everything else
-    patch_all = np.flatnonzero(~special)
-    patch_idx = patch_all[: npb * b]
-    special_idx = np.sort(np.concatenate([patch_all[npb * b:], np.flatnonzero(special)]))
+    patch_idx = np.flatnonzero(~special)
+    special_idx = np.flatnonzero(special)
+    n_patch = patch_idx.size
+    npb = -(-n_patch // b)                      # patch blocks, the last one ragged unless b divides N_p
+    nb = npb + -(-special_idx.size // b)
     plan = B.SpecialTokenPlan(torch.from_numpy(special), b, "cuda")
-    assert plan.n_patch_blocks == npb
+    assert plan.n_patch_blocks == npb and plan.n_blocks == nb and plan.n_patch == n_patch
     tq, tk, tv = (to_device(x, cfg.dtype) for x in (q, k, v))
     out, idx, cnt, bits = B.sparse_global_attention_special(tq, tk, tv, plan, tau, rho)
     torch.cuda.synchronize()
-    blocks = list(range(npb)) if patch_blocks is None else [I for I in patch_blocks if I < npb]
+    blocks = list(range(npb)) if patch_blocks is None else sorted({I % npb for I in patch_blocks})
     want, want_mask = O.special_token_attention(q, k, v, patch_idx, special_idx, b, tau, rho, patch_blocks=blocks)
-    # block map: rows/columns of the pure patch blocks against the oracle's patch-only map
-    nb = -(-N // b)
+    # block map: rows/columns of the patch blocks against the oracle's patch-only map
     mask = bits_to_mask(bits, nb)
     assert (lists_to_mask(idx, cnt, nb) == mask).all()
     assert mask[:, npb:, :].all() and mask[:, :, npb:].all(), "special rows and columns must be dense"
@@ -134,10 +134,12 @@ def test_layer_fp32_config1_shape(B):
     assert mx <= 1e-5 and mean <= 1e-6
 
 
-def test_layer_full_size_100_frames_sampled(B):
-    """Headline shape with the split, one head; sampled patch blocks (first, last, a few inside) and
-    all 500 special rows plus the left-over patch rows."""
+@pytest.mark.parametrize("tau,rho", [(0.9, 1.0), (0.0, 0.75)])
+def test_layer_full_size_100_frames_sampled(B, tau, rho):
+    """Headline shape with the split, two heads; sampled patch blocks (first, a few inside, the last
+    full one and the ragged last one: 136,900 patch tokens = 1069 blocks + 68 tokens) and all 500
+    special rows."""
     cfg = CONFIGS[4]
-    mx, mean, kept = _run_layer(B, cfg, heads=1, frames=cfg.frames, tau=0.9, rho=1.0,
-                                patch_blocks=[0, 1, 517, 1067, 1068])
+    mx, mean, kept = _run_layer(B, cfg, heads=2, frames=cfg.frames, tau=tau, rho=rho,
+                                patch_blocks=[0, 1, 517, 1067, 1068, 1069])
     assert mx <= 1e-2 and mean <= 1e-3
