@@ -156,6 +156,26 @@ int bsga_sparse_attn(const void* q, const void* k, const void* v, int dtype, int
                      float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * bsga_sparse_attn for callers that cannot allocate or hand over device memory beyond the tensors
+ * themselves: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments and results as bsga_sparse_attn without the workspace: the launch order of the rows
+ * lives in a buffer built into the library (bsga_noalloc_scratch_bytes() bytes of device memory per
+ * GPU, held from the first call on that GPU until the process ends).  The call allocates and frees
+ * nothing and clears nothing with a memset.  Shapes whose launch order does not fit, i.e.
+ * bsga_attn_workspace_bytes(...) > bsga_noalloc_scratch_bytes(), return BSGA_ERR_UNSUPPORTED (the
+ * buffer holds heads * (ceil(n_tokens/64) + 33) + 4 <= 524288 words: e.g. 16 heads x 2 million
+ * tokens).  All calls on one GPU share the one buffer and each overwrites it: calls that overlap in
+ * time on the same GPU (different streams, or different threads) race; order them on one stream.
+ */
+int bsga_sparse_attn_noalloc(const void* q, const void* k, const void* v, int dtype, int heads,
+                             int64_t n_tokens, int head_dim, int block, float softmax_scale,
+                             const int32_t* kv_idx, const int32_t* kv_cnt, int idx_stride, void* out,
+                             float* lse, void* stream);
+
+/* Size in bytes of the built-in buffer of bsga_sparse_attn_noalloc (a constant of the build). */
+size_t bsga_noalloc_scratch_bytes(void);
+
+/*
  * Block-sparse attention with separate query and key block sizes (the appendix's learned-projection
  * ablation predicts its maps with query blocks of 128 and key blocks of 64; Sec. 4.1 otherwise).
  * As bsga_sparse_attn, but query block I covers block_q tokens and the lists refer to key blocks of

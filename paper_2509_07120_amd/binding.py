@@ -37,6 +37,8 @@ EXPORTED_SYMBOLS = (
     "bsga_gather_tokens",
     "bsga_attn_workspace_bytes",
     "bsga_sparse_attn",
+    "bsga_sparse_attn_noalloc",
+    "bsga_noalloc_scratch_bytes",
     "bsga_sparse_attn_qk",
     "bsga_sparse_attn_split",
     "bsga_dense_attn",
@@ -80,6 +82,11 @@ def _load() -> ctypes.CDLL:
     lib.bsga_sparse_attn.restype = c_int
     lib.bsga_sparse_attn.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int64, c_int, c_int, c_float,
                                      c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.bsga_sparse_attn_noalloc.restype = c_int
+    lib.bsga_sparse_attn_noalloc.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int64, c_int, c_int, c_float,
+                                             c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_void_p]
+    lib.bsga_noalloc_scratch_bytes.restype = c_size_t
+    lib.bsga_noalloc_scratch_bytes.argtypes = []
     lib.bsga_sparse_attn_qk.restype = c_int
     lib.bsga_sparse_attn_qk.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int64, c_int, c_int, c_int, c_float,
                                         c_void_p, c_void_p, c_int, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
@@ -243,6 +250,24 @@ def bsga_sparse_attn(q, k, v, block: int, kv_idx: torch.Tensor, kv_cnt: torch.Te
                                        float(softmax_scale), _ptr(kv_idx), _ptr(kv_cnt), kv_idx.shape[-1], _ptr(out),
                                        _ptr(lse), _ptr(workspace), ws_bytes, _stream(q)))
     return (out, lse) if return_lse else out
+
+
+def bsga_noalloc_scratch_bytes() -> int:
+    return int(lib.bsga_noalloc_scratch_bytes())
+
+
+def bsga_sparse_attn_noalloc(q, k, v, block: int, kv_idx: torch.Tensor, kv_cnt: torch.Tensor, out: torch.Tensor,
+                             softmax_scale: Optional[float] = None, lse: Optional[torch.Tensor] = None):
+    """bsga_sparse_attn on the library's built-in scratch: nothing is allocated here either (the
+    caller passes `out`, and `lse` [H, N] float32 if wanted)."""
+    _require(q, "q"); _require(k, "k", q.dtype); _require(v, "v", q.dtype); _require(out, "out", q.dtype)
+    _require(kv_idx, "kv_idx", torch.int32); _require(kv_cnt, "kv_cnt", torch.int32)
+    H, N, d = q.shape
+    if softmax_scale is None:
+        softmax_scale = 1.0 / math.sqrt(d)
+    _check(lib.bsga_sparse_attn_noalloc(_ptr(q), _ptr(k), _ptr(v), _dtype_code(q), H, N, d, block, float(softmax_scale),
+                                        _ptr(kv_idx), _ptr(kv_cnt), kv_idx.shape[-1], _ptr(out), _ptr(lse), _stream(q)))
+    return out
 
 
 def bsga_sparse_attn_split(q, k, v, block: int, n_first: int, kv_idx: torch.Tensor, kv_cnt: torch.Tensor,

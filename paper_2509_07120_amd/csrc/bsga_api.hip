@@ -4,7 +4,15 @@
 #include <stdarg.h>
 #include <stdio.h>
 
+#include <mutex>
+
 #include "bsga_internal.h"
+
+// Scratch of bsga_sparse_attn_noalloc: the launch order of the (head, query block) rows and the
+// class table that builds it.  Every GPU the library runs on holds its own copy for the life of the
+// process; host code reaches it only through the per-device address taken below, never by name.
+constexpr size_t kStaticScratchBytes = size_t(2) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace bsga {
 
@@ -95,6 +103,26 @@ static int attn_common(const char* fn, const void* q, const void* k, const void*
   return launch_attn_fp32(static_cast<const float*>(q), static_cast<const float*>(k), static_cast<const float*>(v),
                           heads, n_tokens, n_first, block, softmax_scale, kv_idx, kv_cnt, idx_stride,
                           static_cast<float*>(out), lse, s);
+}
+
+// Device address of `scratch` on the current device, looked up once per device.
+static int static_scratch(const char* fn, void** ptr) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* addr[kMaxDevices] = {};
+  int dev = -1;
+  if (int rc = check_hip(hipGetDevice(&dev), "hipGetDevice")) return rc;
+  if (dev < 0 || dev >= kMaxDevices)
+    return fail(BSGA_ERR_UNSUPPORTED, "%s: device ordinal %d is outside [0, %d)", fn, dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(mu);
+  if (addr[dev] == nullptr) {
+    void* p = nullptr;
+    if (int rc = check_hip(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)")) return rc;
+    if (p == nullptr) return fail(BSGA_ERR_HIP, "%s: hipGetSymbolAddress returned a null address", fn);
+    addr[dev] = p;
+  }
+  *ptr = addr[dev];
+  return BSGA_OK;
 }
 
 }  // namespace bsga
@@ -204,6 +232,28 @@ int bsga_sparse_attn(const void* q, const void* k, const void* v, int dtype, int
   }
   return attn_common("bsga_sparse_attn", q, k, v, dtype, heads, n_tokens, n_tokens, head_dim, block, block, softmax_scale,
                      kv_idx, kv_cnt, idx_stride, out, lse, workspace, workspace_bytes, stream);
+}
+
+size_t bsga_noalloc_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int bsga_sparse_attn_noalloc(const void* q, const void* k, const void* v, int dtype, int heads, int64_t n_tokens,
+                             int head_dim, int block, float softmax_scale, const int32_t* kv_idx,
+                             const int32_t* kv_cnt, int idx_stride, void* out, float* lse, void* stream) {
+  const char* fn = "bsga_sparse_attn_noalloc";
+  clear_error();
+  if (!kv_idx || !kv_cnt) return fail(BSGA_ERR_INVALID_ARG, "%s: kv_idx and kv_cnt must be non-null", fn);
+  if (int rc = check_shape(fn, dtype, heads, n_tokens, head_dim)) return rc;
+  const size_t need = attn_workspace(dtype, heads, n_tokens);
+  if (need > kStaticScratchBytes)
+    return fail(BSGA_ERR_UNSUPPORTED,
+                "%s: this shape needs %zu bytes of scratch, the built-in buffer holds %zu (about heads * "
+                "(ceil(n_tokens / 64) + 33) <= %zu); use bsga_sparse_attn with a workspace",
+                fn, need, kStaticScratchBytes, kStaticScratchBytes / sizeof(int32_t));
+  void* ws = nullptr;
+  if (need > 0)
+    if (int rc = static_scratch(fn, &ws)) return rc;
+  return attn_common(fn, q, k, v, dtype, heads, n_tokens, n_tokens, head_dim, block, block, softmax_scale, kv_idx,
+                     kv_cnt, idx_stride, out, lse, ws, ws ? kStaticScratchBytes : 0, stream);
 }
 
 int bsga_sparse_attn_qk(const void* q, const void* k, const void* v, int dtype, int heads, int64_t n_tokens,
