@@ -214,6 +214,22 @@ int bsga_dense_attn(const void* q, const void* k, const void* v, int dtype, int 
                     int64_t n_tokens, int head_dim, float softmax_scale, void* out, float* lse,
                     void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Measurement aid, not part of the method: the rate the matrix pipes sustain on the MFMA instruction
+ * the bf16 attention kernels use (32x32x16 bf16, the products of Eqs. (1)/(2)), with no memory traffic
+ * at all, two workgroups of four waves per CU.  The part lowers its clock with the switching activity
+ * of the data, so this rate on random operands, not the nominal peak, bounds any bf16 kernel.
+ *   operands     0 = all-zero operands, 1 = pseudo-random roughly unit-normal bf16 values
+ *   softmax_mix  0 = MFMAs only; 1 = beside every MFMA the softmax arithmetic attention needs per MFMA
+ *                at head dim 64: two exp2, one pack to bf16, two fp32 adds
+ *   iters        rounds of 8 MFMAs per wave
+ *   sink         device buffer of at least 2 * (number of CUs) * 1024 bytes, overwritten
+ *   flops        nullable host pointer: receives the FLOPs of the launch (2 * 32*32*16 per MFMA)
+ * The call only enqueues the kernel on `stream`; the caller times it.
+ */
+int bsga_probe_mfma(int operands, int softmax_mix, int iters, void* sink, size_t sink_bytes,
+                    double* flops, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

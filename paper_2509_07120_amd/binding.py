@@ -42,6 +42,7 @@ EXPORTED_SYMBOLS = (
     "bsga_sparse_attn_qk",
     "bsga_sparse_attn_split",
     "bsga_dense_attn",
+    "bsga_probe_mfma",
 )
 
 
@@ -97,6 +98,8 @@ def _load() -> ctypes.CDLL:
     lib.bsga_dense_attn.restype = c_int
     lib.bsga_dense_attn.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int64, c_int, c_float,
                                     c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.bsga_probe_mfma.restype = c_int
+    lib.bsga_probe_mfma.argtypes = [c_int, c_int, c_int, c_void_p, c_size_t, ctypes.POINTER(c_double), c_void_p]
     return lib
 
 
@@ -137,15 +140,23 @@ def num_blocks(n_tokens: int, block: int) -> int:
     return (n_tokens + block - 1) // block
 
 
-def bsga_pool_qk(q: torch.Tensor, k: torch.Tensor, block: int) -> Tuple[torch.Tensor, torch.Tensor]:
-    """q, k [H, N, 64] -> (q_pool, k_pool) [H, ceil(N/block), 64] float64."""
+def bsga_pool_qk(q: torch.Tensor, k: torch.Tensor, block: int,
+                 out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """q, k [H, N, 64] -> (q_pool, k_pool) [H, ceil(N/block), 64] float64 (written into `out` if given)."""
     _require(q, "q"); _require(k, "k", q.dtype)
     if q.shape != k.shape or q.dim() != 3:
         raise ValueError("q and k must both be [heads, n_tokens, head_dim]")
     H, N, d = q.shape
     nb = num_blocks(N, block)
-    q_pool = torch.empty((H, nb, d), dtype=torch.float64, device=q.device)
-    k_pool = torch.empty_like(q_pool)
+    if out is None:
+        q_pool = torch.empty((H, nb, d), dtype=torch.float64, device=q.device)
+        k_pool = torch.empty_like(q_pool)
+    else:
+        q_pool, k_pool = out
+        for t in (q_pool, k_pool):
+            _require(t, "out", torch.float64)
+            if tuple(t.shape) != (H, nb, d):
+                raise ValueError(f"out tensors must be {(H, nb, d)}")
     _check(lib.bsga_pool_qk(_ptr(q), _ptr(k), _dtype_code(q), H, N, d, block, _ptr(q_pool), _ptr(k_pool), _stream(q)))
     return q_pool, k_pool
 
@@ -155,15 +166,23 @@ def split_blocks(n_tokens: int, n_first: int, block: int) -> int:
     return num_blocks(n_first, block) + num_blocks(n_tokens - n_first, block)
 
 
-def bsga_pool_qk_split(q: torch.Tensor, k: torch.Tensor, block: int, n_first: int) -> Tuple[torch.Tensor, torch.Tensor]:
+def bsga_pool_qk_split(q: torch.Tensor, k: torch.Tensor, block: int, n_first: int,
+                       out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None) -> Tuple[torch.Tensor, torch.Tensor]:
     """As bsga_pool_qk for a sequence split at token n_first: no block crosses n_first."""
     _require(q, "q"); _require(k, "k", q.dtype)
     if q.shape != k.shape or q.dim() != 3:
         raise ValueError("q and k must both be [heads, n_tokens, head_dim]")
     H, N, d = q.shape
     nb = split_blocks(N, n_first, block) if 0 <= n_first <= N else 1
-    q_pool = torch.empty((H, nb, d), dtype=torch.float64, device=q.device)
-    k_pool = torch.empty_like(q_pool)
+    if out is None:
+        q_pool = torch.empty((H, nb, d), dtype=torch.float64, device=q.device)
+        k_pool = torch.empty_like(q_pool)
+    else:
+        q_pool, k_pool = out
+        for t in (q_pool, k_pool):
+            _require(t, "out", torch.float64)
+            if tuple(t.shape) != (H, nb, d):
+                raise ValueError(f"out tensors must be {(H, nb, d)}")
     _check(lib.bsga_pool_qk_split(_ptr(q), _ptr(k), _dtype_code(q), H, N, n_first, d, block, _ptr(q_pool),
                                   _ptr(k_pool), _stream(q)))
     return q_pool, k_pool
@@ -181,9 +200,10 @@ def bsga_pool(x: torch.Tensor, block: int) -> torch.Tensor:
 def bsga_select_blocks(q_pool: torch.Tensor, k_pool: torch.Tensor, tau: float, rho: float = 1.0,
                        score_scale: Optional[float] = None, force_q: Optional[torch.Tensor] = None,
                        force_k: Optional[torch.Tensor] = None, want_bits: bool = True,
-                       workspace: Optional[torch.Tensor] = None):
+                       workspace: Optional[torch.Tensor] = None, out=None):
     """Pooled Q/K -> (mask_bits [H,nbq,ceil(nbk/32)] uint32-as-int32, kv_idx [H,nbq,nbk] int32, kv_cnt [H,nbq] int32).
-    `workspace`: optional device byte buffer of bsga_select_workspace_bytes(H, nbq, nbk) bytes (allocated if absent)."""
+    `workspace`: optional device byte buffer of bsga_select_workspace_bytes(H, nbq, nbk) bytes (allocated if absent).
+    `out`: optional (mask_bits or None, kv_idx, kv_cnt) tensors of those shapes to write into."""
     _require(q_pool, "q_pool", torch.float64); _require(k_pool, "k_pool", torch.float64)
     H, nbq, d = q_pool.shape
     nbk = k_pool.shape[1]
@@ -191,9 +211,20 @@ def bsga_select_blocks(q_pool: torch.Tensor, k_pool: torch.Tensor, tau: float, r
         score_scale = 1.0 / math.sqrt(d)
     dev = q_pool.device
     words = (nbk + 31) // 32
-    mask_bits = torch.zeros((H, nbq, words), dtype=torch.int32, device=dev) if want_bits else None
-    kv_idx = torch.empty((H, nbq, nbk), dtype=torch.int32, device=dev)
-    kv_cnt = torch.empty((H, nbq), dtype=torch.int32, device=dev)
+    if out is None:
+        # every word of every row is written by the kernel, so nothing needs to be cleared
+        mask_bits = torch.empty((H, nbq, words), dtype=torch.int32, device=dev) if want_bits else None
+        kv_idx = torch.empty((H, nbq, nbk), dtype=torch.int32, device=dev)
+        kv_cnt = torch.empty((H, nbq), dtype=torch.int32, device=dev)
+    else:
+        mask_bits, kv_idx, kv_cnt = out
+        for t, shape, name in ((mask_bits, (H, nbq, words), "mask_bits"), (kv_idx, (H, nbq, nbk), "kv_idx"),
+                               (kv_cnt, (H, nbq), "kv_cnt")):
+            if t is None and name == "mask_bits":
+                continue
+            _require(t, name, torch.int32)
+            if tuple(t.shape) != shape:
+                raise ValueError(f"{name} must be {shape}, got {tuple(t.shape)}")
     if force_q is not None:
         _require(force_q, "force_q", torch.uint8)
     if force_k is not None:
@@ -368,3 +399,23 @@ def sparse_global_attention_special(q, k, v, plan: SpecialTokenPlan, tau: float,
                                                    force_k=plan.force_k)
     ow = bsga_sparse_attn_split(qw, kw, vw, plan.block, plan.n_patch, kv_idx, kv_cnt, softmax_scale)
     return bsga_gather_tokens(ow, plan.inverse), kv_idx, kv_cnt, mask_bits
+
+
+def bsga_probe_mfma(operands: int, softmax_mix: bool, iters: int = 20000, repeats: int = 3) -> float:
+    """Sustained TFLOP/s of the attention kernels' MFMA instruction with no memory traffic (see
+    bsga_probe_mfma in the header).  Times `repeats` launches with events and returns the best."""
+    dev = torch.device("cuda", torch.cuda.current_device())
+    sink = torch.empty(2 * torch.cuda.get_device_properties(dev).multi_processor_count * 256, dtype=torch.float32, device=dev)
+    flops = ctypes.c_double(0.0)
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    best = 0.0
+    for r in range(repeats + 1):  # the first launch is a warm-up
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        _check(lib.bsga_probe_mfma(int(operands), int(bool(softmax_mix)), int(iters), _ptr(sink), sink.numel() * 4,
+                                   ctypes.byref(flops), stream))
+        e1.record()
+        torch.cuda.synchronize(dev)
+        if r > 0:
+            best = max(best, flops.value / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    return best

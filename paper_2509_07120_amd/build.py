@@ -10,7 +10,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libbsga.so")
-SOURCES = ["bsga_api.hip", "pool.hip", "select.hip", "gather.hip", "attn_fp32.hip", "attn_bf16.hip"]
+SOURCES = ["bsga_api.hip", "pool.hip", "select.hip", "gather.hip", "attn_fp32.hip", "attn_bf16.hip", "probe.hip"]
 
 
 def hipcc_path() -> str:

@@ -280,6 +280,17 @@ int bsga_sparse_attn_split(const void* q, const void* k, const void* v, int dtyp
                      softmax_scale, kv_idx, kv_cnt, idx_stride, out, lse, workspace, workspace_bytes, stream);
 }
 
+int bsga_probe_mfma(int operands, int softmax_mix, int iters, void* sink, size_t sink_bytes, double* flops,
+                    void* stream) {
+  const char* fn = "bsga_probe_mfma";
+  clear_error();
+  if (operands != 0 && operands != 1) return fail(BSGA_ERR_INVALID_ARG, "%s: operands must be 0 (zeros) or 1 (random)", fn);
+  if (iters < 1 || iters > (1 << 24)) return fail(BSGA_ERR_INVALID_ARG, "%s: iters must be in [1, 2^24], got %d", fn, iters);
+  if (!sink) return fail(BSGA_ERR_INVALID_ARG, "%s: sink must be non-null", fn);
+  return launch_probe_mfma(operands, softmax_mix != 0, iters, static_cast<float*>(sink), sink_bytes, flops,
+                           static_cast<hipStream_t>(stream));
+}
+
 int bsga_dense_attn(const void* q, const void* k, const void* v, int dtype, int heads, int64_t n_tokens,
                     int head_dim, float softmax_scale, void* out, float* lse, void* workspace,
                     size_t workspace_bytes, void* stream) {

@@ -45,4 +45,7 @@ int launch_attn_fp32(const float* q, const float* k, const float* v, int heads, 
                      int block, float softmax_scale, const int32_t* kv_idx, const int32_t* kv_cnt,
                      int idx_stride, float* out, float* lse, hipStream_t stream);
 
+int launch_probe_mfma(int pattern, int mix, int iters, float* sink, size_t sink_bytes, double* flops,
+                      hipStream_t stream);
+
 }  // namespace bsga

@@ -133,3 +133,10 @@ def test_split_argument_errors(B):
     assert "idx_stride" in _err(B)
     assert L.bsga_sparse_attn_split(*args, 130, 64, 64, 128, 0.125, A, A, 16, A, None, None, 0, None) == 2
     assert L.bsga_sparse_attn_split(*args, 130, 64, 128, 128, 0.125, None, A, 16, A, None, None, 0, None) == 1
+
+
+def test_probe_argument_errors(B):
+    L = B.lib
+    assert L.bsga_probe_mfma(2, 0, 10, A, 1 << 20, None, None) == 1 and "operands" in _err(B)
+    assert L.bsga_probe_mfma(0, 0, 0, A, 1 << 20, None, None) == 1 and "iters" in _err(B)
+    assert L.bsga_probe_mfma(0, 0, 10, None, 1 << 20, None, None) == 1 and "sink" in _err(B)

@@ -11,6 +11,10 @@ def test_token_arithmetic():
     assert CONFIGS[5].tokens_per_frame == 1 + 4 + 28 * 37 == 1041
     assert [CONFIGS[i].n_tokens for i in range(1, 6)] == [2748, 10992, 43968, 137400, 312300]
     assert [CONFIGS[i].n_blocks for i in range(1, 6)] == [43, 172, 344, 1074, 2440]
+    # higher-resolution shape: twice the image side -> four times the patches per frame; a quarter of
+    # the frames then gives (almost) the 100-frame token count
+    assert 1036 // 14 == 74 and CONFIGS[6].patches_per_frame == 4 * CONFIGS[4].patches_per_frame
+    assert CONFIGS[6].n_tokens == 25 * (5 + 74 * 74) == 137025 and CONFIGS[6].n_blocks == 1071
     # Sec. 4.1: ten frames at 294x518 -> (10*294*518/14^2)^2 = 7770^2 = 6.04e7 entries; the
     # printed 1.2e8 matches that count in bytes at half precision (">100MB"), not in entries.
     assert (10 * 294 * 518) // 14 ** 2 == 7770

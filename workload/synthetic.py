@@ -1,4 +1,4 @@
-"""Correspondence-structured Q/K/V generator for the five benchmark shapes.
+"""Correspondence-structured Q/K/V generator for the five benchmark shapes and a higher-resolution one.
 
 Token layout per frame (paper, Sec. 3.1 and Fig. 2): one camera token, four
 register tokens, then the patch tokens of a 14x14-pixel patch grid
@@ -60,6 +60,11 @@ CONFIGS: Dict[int, WorkloadConfig] = {
     3: WorkloadConfig(3, "32 frames bf16 b128", 32, 37 * 37, 16, 128, "bf16", 8000, 0.3, (0.9,)),
     4: WorkloadConfig(4, "100 frames bf16 b128", 100, 37 * 37, 16, 128, "bf16", 8000, 0.3, (0.8, 0.9, 0.95)),
     5: WorkloadConfig(5, "300 frames 518x392 bf16 b128", 300, 37 * 28, 16, 128, "bf16", 20000, 0.2, (0.9,)),
+    # Higher-resolution input (the paper's discussion: doubling the image side gives four times the
+    # patch tokens per frame and sixteen times the global-attention cost).  1036x1036 px -> 74x74
+    # patches per frame; 25 frames give about the token count of the 100-frame shape, at a quarter of
+    # the frames and four times the tokens per frame (latent pool scaled with the patches per frame).
+    6: WorkloadConfig(6, "25 frames 1036x1036 bf16 b128", 25, 74 * 74, 16, 128, "bf16", 32000, 0.3, (0.9,)),
 }
 
 
