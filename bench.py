@@ -340,13 +340,16 @@ def main() -> int:
     # the switching activity of the operands; the attention kernel is to be read against these) -------
     probe = None
     if not args.no_probe:
-        probe = {"what": "v_mfma_f32_32x32x16_bf16 only, registers only, 2 workgroups x 4 waves per CU; 'softmax' adds "
-                         "2 exp2 + 1 bf16 pack + 2 fp32 adds per MFMA (the attention kernel's mix at head dim 64)",
+        probe = {"what": "v_mfma_f32_32x32x16_bf16 only, registers only, 2 workgroups x 4 waves per CU; 'softmax' adds, "
+                         "per MFMA, 2 exp2 + 1 bf16 pack and the row sum of the two weights (by 2 fp32 adds, or, as the "
+                         "attention kernel does it, by one 16x16x32 MFMA per 4 products): the mix of head dim 64; the "
+                         "FLOPs counted are those of the 32x32x16 products only",
                  "unit": "TFLOP/s",
-                 "zero_operands": B.bsga_probe_mfma(0, False),
-                 "random_operands": B.bsga_probe_mfma(1, False),
-                 "zero_operands_softmax": B.bsga_probe_mfma(0, True),
-                 "random_operands_softmax": B.bsga_probe_mfma(1, True)}
+                 "zero_operands": B.bsga_probe_mfma(0, 0),
+                 "random_operands": B.bsga_probe_mfma(1, 0),
+                 "random_operands_softmax_adds": B.bsga_probe_mfma(1, 1),
+                 "zero_operands_softmax": B.bsga_probe_mfma(0, 2),
+                 "random_operands_softmax": B.bsga_probe_mfma(1, 2)}
         print("[bench] mfma probe: " + json.dumps({k: v for k, v in probe.items() if k not in ("what", "unit")}),
               file=sys.stderr, flush=True)
     w = Workload(B, torch, cfg)

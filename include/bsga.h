@@ -221,7 +221,9 @@ int bsga_dense_attn(const void* q, const void* k, const void* v, int dtype, int 
  * of the data, so this rate on random operands, not the nominal peak, bounds any bf16 kernel.
  *   operands     0 = all-zero operands, 1 = pseudo-random roughly unit-normal bf16 values
  *   softmax_mix  0 = MFMAs only; 1 = beside every MFMA the softmax arithmetic attention needs per MFMA
- *                at head dim 64: two exp2, one pack to bf16, two fp32 adds
+ *                at head dim 64: two exp2, one pack to bf16, two fp32 adds for the row sum;
+ *                2 = the same with the row sums taken the way the attention kernel takes them, by one
+ *                16x16x32 MFMA per four products instead of the adds
  *   iters        rounds of 8 MFMAs per wave
  *   sink         device buffer of at least 2 * (number of CUs) * 1024 bytes, overwritten
  *   flops        nullable host pointer: receives the FLOPs of the launch (2 * 32*32*16 per MFMA)

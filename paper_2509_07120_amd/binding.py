@@ -401,7 +401,7 @@ def sparse_global_attention_special(q, k, v, plan: SpecialTokenPlan, tau: float,
     return bsga_gather_tokens(ow, plan.inverse), kv_idx, kv_cnt, mask_bits
 
 
-def bsga_probe_mfma(operands: int, softmax_mix: bool, iters: int = 20000, repeats: int = 3) -> float:
+def bsga_probe_mfma(operands: int, softmax_mix: int, iters: int = 20000, repeats: int = 3) -> float:
     """Sustained TFLOP/s of the attention kernels' MFMA instruction with no memory traffic (see
     bsga_probe_mfma in the header).  Times `repeats` launches with events and returns the best."""
     dev = torch.device("cuda", torch.cuda.current_device())
@@ -412,7 +412,7 @@ def bsga_probe_mfma(operands: int, softmax_mix: bool, iters: int = 20000, repeat
     for r in range(repeats + 1):  # the first launch is a warm-up
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        _check(lib.bsga_probe_mfma(int(operands), int(bool(softmax_mix)), int(iters), _ptr(sink), sink.numel() * 4,
+        _check(lib.bsga_probe_mfma(int(operands), int(softmax_mix), int(iters), _ptr(sink), sink.numel() * 4,
                                    ctypes.byref(flops), stream))
         e1.record()
         torch.cuda.synchronize(dev)

@@ -44,6 +44,8 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
@@ -71,22 +73,21 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
 __device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32); }
 
 // 16 bytes per lane from a raw buffer straight into LDS (buffer_load_dwordx4 ... lds): lane i's
-// data lands at LDS byte address lds_addr + 16 i.  voff is the per-lane byte offset, soff a
+// data lands at LDS byte address lds_base + lds_imm + 16 i.  voff is the per-lane byte offset, soff a
 // wave-uniform one; lanes whose offset is past the buffer's size get zeros.  Written as inline
 // assembly on purpose: the compiler then does not count these loads as LDS writes and so does not
 // make later LDS reads of the *other* buffer wait for them; the kernel orders them itself
-// (s_waitcnt vmcnt + barrier).  M0 (the LDS base of the load) is put back afterwards.
-__device__ __forceinline__ void dma16(i32x4 rsrc, unsigned voff, unsigned soff, unsigned lds_addr) {
-  unsigned saved_m0;
+// (s_waitcnt vmcnt + barrier).  M0 (the LDS base of the load) is declared clobbered; nothing else in
+// these kernels uses it.
+template <unsigned LDS_IMM>
+__device__ __forceinline__ void dma16(i32x4 rsrc, unsigned voff, unsigned soff, unsigned lds_base) {
   asm volatile(
-      "s_mov_b32 %0, m0\n\t"
-      "s_mov_b32 m0, %1\n\t"
+      "s_add_u32 m0, %0, %4\n\t"
       "s_nop 0\n\t"  // one wait state between a scalar write of M0 and an LDS-DMA instruction that reads it
-      "buffer_load_dwordx4 %2, %3, %4 offen lds\n\t"
-      "s_mov_b32 m0, %0"
-      : "=&s"(saved_m0)
-      : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
-      : "memory");
+      "buffer_load_dwordx4 %1, %2, %3 offen lds"
+      :
+      : "s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff), "n"(LDS_IMM)
+      : "memory", "m0", "scc");
 }
 
 // raw buffer descriptor over [base, base + bytes): stride 0, 32-bit element data format
@@ -397,30 +398,36 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   // With half-tile key blocks, loads i = 0, 1 fill tile rows 0..63 from block a and i = 2, 3 rows
   // 64..127 from block b; an absent b gets an offset past the end of the buffer, so the bounds check
   // zero-fills that half.
-  auto issue_part = [&](const Tile& J, int buf, int i2) {
-    const int i = i2 >> 1;
-    const bool is_v = (i2 & 1) != 0;
-    const unsigned dst = smem_addr + wave * 1024 + NW * i * 1024 + (is_v ? V_BASE : 0) + buf * TILE_BYTES;
+  const unsigned dma_base = smem_addr + wave * 1024;  // this wave's 1 KB slice of every 4 KB (8 KB) group
+  auto issue_part = [&](const Tile& J, auto bufc, auto i2c) {
+    constexpr int buf = decltype(bufc)::value, i2 = decltype(i2c)::value;
+    constexpr int i = i2 >> 1;
+    constexpr bool is_v = (i2 & 1) != 0;
+    constexpr unsigned dst = NW * i * 1024 + (is_v ? V_BASE : 0) + buf * TILE_BYTES;
     if constexpr (HALF) {
       const int Jx = (i >> 1) ? J.b : J.a;
       const unsigned soff = Jx < 0 ? head_size : static_cast<unsigned>(key_start(Jx)) * 128u;
       if (is_v) {
-        dma16(vrsrc, voff, soff + (Jx < 0 ? 0u : (i & 1) * NW * 1024), dst);
+        dma16<dst>(vrsrc, voff, soff + (Jx < 0 ? 0u : (i & 1) * NW * 1024), dma_base);
       } else {
-        dma16(krsrc, koff[i % KN], soff, dst);
+        dma16<dst>(krsrc, koff[i % KN], soff, dma_base);
       }
     } else {
       const unsigned soff = static_cast<unsigned>(key_start(J.a)) * 128u;
       if (is_v) {
-        dma16(vrsrc, voff, soff + i * NW * 1024, dst);
+        dma16<dst>(vrsrc, voff, soff + i * NW * 1024, dma_base);
       } else {
-        dma16(krsrc, koff[i % KN], soff + (i / KN) * KN * NW * 1024, dst);
+        dma16<dst>(krsrc, koff[i % KN], soff + (i / KN) * KN * NW * 1024, dma_base);
       }
     }
   };
-  auto issue = [&](const Tile& J, int buf) {
-#pragma unroll
-    for (int i2 = 0; i2 < 8; ++i2) issue_part(J, buf, i2);
+  auto issue = [&](const Tile& J, auto bufc) {
+    issue_part(J, bufc, Int<0>{}); issue_part(J, bufc, Int<1>{}); issue_part(J, bufc, Int<2>{}); issue_part(J, bufc, Int<3>{});
+    issue_part(J, bufc, Int<4>{}); issue_part(J, bufc, Int<5>{}); issue_part(J, bufc, Int<6>{}); issue_part(J, bufc, Int<7>{});
+  };
+  auto issue_rt = [&](const Tile& J, int buf) {  // buffer known at run time only
+    if (buf) issue(J, Int<1>{});
+    else issue(J, Int<0>{});
   };
 
   // K operands (A of S^T = K Q^T) of the wave's 32-key sub-tile u; boff = byte offset of the buffer
@@ -518,7 +525,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   auto plain_loop = [&](auto safec) {
     if (ntiles <= 0) return;
     Tile J_cur = block_at(0);
-    issue(J_cur, 0);
+    issue(J_cur, Int<0>{});
     Tile J_pre = raw_at(1);  // list entries are fetched a tile before they are used
     bf16x8 ka[4], va[2][2];
     f32x16 sc;
@@ -528,7 +535,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
       const Tile J_next = (it + 1 < ntiles) ? fix(J_pre, it + 1) : Tile{0, -1};
       __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile `it` has landed
       __syncthreads();                     // ... and so has everyone else's; buffer buf^1 is free
-      if (it + 1 < ntiles) issue(J_next, buf ^ 1);
+      if (it + 1 < ntiles) issue_rt(J_next, buf ^ 1);
       // The list entries of the tile after next.  Scalar loads return out of order with LDS reads, so
       // a wait for LDS data would also wait for them: they are issued where every LDS read of the
       // tile has been consumed, and used at the top of the next tile.
@@ -563,6 +570,28 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     bf16x8 ka[4];        // K operands of the sub-tile whose scores are computed next
     bf16x8 va[2][2][2];  // V^T operands: [sub-tile][dim block][16-key chunk]
     float ex[2][2];      // exponentiated scores of the key pair that is packed in the next slot
+    // Row sums on the matrix pipe.  In v_mfma_f32_16x16x32_bf16 lane l supplies, as B operand, eight
+    // bf16 values B[k][j] of column j = l%16 with k = 8(l/16) .. 8(l/16)+7, supplies row l%16 of A for
+    // the same eight k, and receives D[4(l/16) + r][l%16] in accumulator register r = 0..3.  With
+    //   A_h[i][k] = 1 if i%4 == h and k/8 == i/4, else 0
+    // the product D = A_h B puts, in register h of every lane, the sum of that lane's own eight B
+    // values, and nothing in the other registers.  The B operand is the very register tuple of packed
+    // weights that the O update multiplies with V, so two such instructions per unit (h = the query
+    // half) sum the sixteen weights a lane holds: they replace sixteen fp32 adds per unit (64 cycles
+    // of vector issue in a loop whose vector and matrix pipes are both saturated) by 32 cycles of
+    // matrix pipe, and the sums are over the bf16 weights, exactly the values that multiply V.
+    f32x4 lacc = {0.f, 0.f, 0.f, 0.f};
+    bf16x8 row_sel[2];
+#pragma unroll
+    for (int h2 = 0; h2 < 2; ++h2) {
+      const bool on = (lane & 3) == h2 && (lane >> 4) == ((lane & 15) >> 2);
+      const unsigned w1 = on ? 0x3F803F80u : 0u;  // two bf16 ones
+      row_sel[h2] = __builtin_bit_cast(bf16x8, u32x4{w1, w1, w1, w1});
+    }
+    auto add_weights = [&](auto hc, const u32x4& words) {
+      lacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(row_sel[decltype(hc)::value], __builtin_bit_cast(bf16x8, words), lacc, 0,
+                                                      0, 0);
+    };
 
     // one unit N = (sub-tile N/2, query half N%2).  Slots 0..3: MFMA of QK(N+1) + one weight pair;
     // slots 4..7: MFMA of PV(N-1) + one weight pair.  mid(slot) places LDS reads, the barrier and
@@ -601,7 +630,9 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
         ex[0][1] = __builtin_amdgcn_exp2f(sc[BN][1]);                                                          \
       }                                                                                                        \
       __builtin_amdgcn_sched_barrier(0);                                                                       \
-      l_run[BQ] += ex[(S_) & 1][0] + ex[(S_) & 1][1];                                                          \
+      /* row sums: the previous unit's second group of weights in slot 1, this unit's first in slot 5 */    \
+      if constexpr ((S_) == 1) add_weights(Int<BP>{}, pw[BP][1]);                                              \
+      if constexpr ((S_) == 5) add_weights(Int<BQ>{}, pw[BQ][0]);                                              \
       pw[BQ][(S_) >> 2][(S_) & 3] = pk;                                                                        \
     }                                                                                                          \
     mid(Int<(S_)>{});                                                                                          \
@@ -616,8 +647,9 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     // V operands of the previous tile's unit 3 (zeros at the start of a run).  What it prepares for
     // the following tile (K operands and first scores from the other buffer) goes unused when the run
     // ends here.
-    auto tile = [&](const Tile& J_next2, int buf) {
-      const unsigned boff = buf * TILE_BYTES;
+    auto tile = [&](const Tile& J_next2, auto bufc) {
+      constexpr int buf = decltype(bufc)::value;
+      constexpr unsigned boff = buf * TILE_BYTES;
       unit(Int<0>{}, [&](auto slot) {  // QK(1); K(u1); PV(previous 3); V(u0)
         constexpr int S = decltype(slot)::value;
         if constexpr (S == 0) read_v(va[0], boff, 0);
@@ -634,21 +666,21 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
           __syncthreads();                     // every read of this tile is complete in every wave
         }
         if constexpr (S == 3) read_k(ka, boff ^ TILE_BYTES, 0);
-        if constexpr (S >= 4) issue_part(J_next2, buf, S - 4);
+        if constexpr (S >= 4) issue_part(J_next2, bufc, Int<S - 4>{});
       });
       unit(Int<3>{}, [&](auto slot) {  // QK(next tile's unit 0); PV(2) + loads 4..7
         constexpr int S = decltype(slot)::value;
-        if constexpr (S >= 4) issue_part(J_next2, buf, S);
+        if constexpr (S >= 4) issue_part(J_next2, bufc, slot);
       });
     };
 
     // ---- tiles 0 and 1 on their way ----------------------------------------------------------------
     Tile J_cur = block_at(0);
-    issue(J_cur, 0);
+    issue(J_cur, Int<0>{});
     Tile J_nxt = J_cur;
     if (ntiles > 1) {
       J_nxt = block_at(1);
-      issue(J_nxt, 1);
+      issue(J_nxt, Int<1>{});
     }
     Tile J_pre = raw_at(2);  // fetched one tile before it becomes "the tile after next"
     __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -675,22 +707,30 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
       ex[0][0] = __builtin_amdgcn_exp2f(sc[0][0]);
       ex[0][1] = __builtin_amdgcn_exp2f(sc[0][1]);
       __builtin_amdgcn_sched_barrier(0);
-      do {
+      // two tiles per round, so that every LDS address is a constant of the code (even tiles lie in
+      // buffer pair 0, odd ones in pair 1)
+      auto step = [&](auto bufc) {
         // the tile after next; at the end of the list one more (harmless) load of a valid tile
         const Tile J2 = (T + 2 < ntiles) ? fix(J_pre, T + 2) : J_cur;
         J_pre = raw_at(T + 3);
-        tile(J2, T & 1);
+        tile(J2, bufc);
         J_cur = J_nxt;
         J_nxt = J2;
         ++T;
-      } while (T < ntiles && !tile_ragged(J_cur));
-      // ---- the O update of the run's last unit --------------------------------------------------------
+        return T < ntiles && !tile_ragged(J_cur);
+      };
+      while (step(Int<0>{}) && step(Int<1>{})) {
+      }
+      // ---- the O update and the last row-sum step of the run's last unit ------------------------------
 #pragma unroll
       for (int db = 0; db < 2; ++db)
 #pragma unroll
         for (int cp = 0; cp < 2; ++cp)
           o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[1][db][cp], __builtin_bit_cast(bf16x8, pw[1][cp]),
                                                              o[db][1], 0, 0, 0);
+      add_weights(Int<1>{}, pw[1][1]);
+      l_run[0] += lacc[0];
+      l_run[1] += lacc[1];
     }
     // ---- from the first ragged tile on: plain tiles (the same buffers and the same one barrier per
     // tile; the loads stay two tiles ahead) ------------------------------------------------------------
@@ -700,7 +740,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
       J_pre = raw_at(T + 3);
       __builtin_amdgcn_s_waitcnt(0x0F70);  // this wave's share of tile T+1 has landed
       __syncthreads();                     // ... everyone's has, and nobody still reads tile T
-      issue(J2, T & 1);
+      issue_rt(J2, T & 1);
       J_cur = J_nxt;
       J_nxt = J2;
     }

@@ -285,9 +285,10 @@ int bsga_probe_mfma(int operands, int softmax_mix, int iters, void* sink, size_t
   const char* fn = "bsga_probe_mfma";
   clear_error();
   if (operands != 0 && operands != 1) return fail(BSGA_ERR_INVALID_ARG, "%s: operands must be 0 (zeros) or 1 (random)", fn);
+  if (softmax_mix < 0 || softmax_mix > 2) return fail(BSGA_ERR_INVALID_ARG, "%s: softmax_mix must be 0, 1 or 2", fn);
   if (iters < 1 || iters > (1 << 24)) return fail(BSGA_ERR_INVALID_ARG, "%s: iters must be in [1, 2^24], got %d", fn, iters);
   if (!sink) return fail(BSGA_ERR_INVALID_ARG, "%s: sink must be non-null", fn);
-  return launch_probe_mfma(operands, softmax_mix != 0, iters, static_cast<float*>(sink), sink_bytes, flops,
+  return launch_probe_mfma(operands, softmax_mix, iters, static_cast<float*>(sink), sink_bytes, flops,
                            static_cast<hipStream_t>(stream));
 }
 

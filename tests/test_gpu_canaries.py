@@ -96,8 +96,8 @@ def test_half_tile_key_blocks_stay_in_bounds(B):
 def test_mfma_probe_runs_and_reports_a_plausible_rate(B):
     """The instruction-rate probe: finishes, and its rates are ordered as the hardware dictates (zero
     operands are not slower than random ones; extra vector work does not make the MFMAs faster)."""
-    zero = B.bsga_probe_mfma(0, False, iters=2000, repeats=2)
-    rand = B.bsga_probe_mfma(1, False, iters=2000, repeats=2)
-    mix = B.bsga_probe_mfma(1, True, iters=2000, repeats=2)
+    zero = B.bsga_probe_mfma(0, 0, iters=2000, repeats=2)
+    rand = B.bsga_probe_mfma(1, 0, iters=2000, repeats=2)
+    mix = min(B.bsga_probe_mfma(1, 1, iters=2000, repeats=2), B.bsga_probe_mfma(1, 2, iters=2000, repeats=2))
     print(f"mfma probe: zero {zero:.0f}, random {rand:.0f}, random + softmax arithmetic {mix:.0f} TFLOP/s")
     assert 300.0 < mix <= rand * 1.05 and rand <= zero * 1.05 and zero < 2600.0
