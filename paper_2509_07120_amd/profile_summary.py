@@ -5,6 +5,7 @@ Usage (from the repository root, after the rocprofv3 runs listed in each summary
     python -m paper_2509_07120_amd.profile_summary stats   <dir of --kernel-trace --stats run> <bench json of that run>
     python -m paper_2509_07120_amd.profile_summary traffic <dir FETCH_SIZE run> <dir WRITE_SIZE run> <dir TCC run>
     python -m paper_2509_07120_amd.profile_summary pipes   <dir of counter run A> <dir of counter run B> ...
+    python -m paper_2509_07120_amd.profile_summary topk    <dir TCC run at rho 0.9> <dir pipe-counter run at rho 0.9>
 
 Each sub-command reads the `*_kernel_stats.csv`, `*_kernel_trace.csv` or `*_counter_collection.csv`
 files rocprofv3 wrote with `--output-format csv`, prints what it found, and rewrites the matching
@@ -275,6 +276,45 @@ SQ_WAVE_CYCLES counts, in units of 4 cycles, the time waves are resident; the "w
     print(open(path).read())
 
 
+# ---------------------------------------------------------------------------------------------- topk
+def cmd_topk(d_tcc: str, d_pipes: str) -> None:
+    """Counters of the short-row regime (top-k only, rho = 0.9) next to the dense launch of the same run."""
+    T = [x for x in dispatches(d_tcc) if "attn_bf16" in x["name"]]
+    P = [x for x in dispatches(d_pipes) if "attn_bf16" in x["name"]]
+    n_sparse = 3
+    cmd = ("cd /tmp && export TMPDIR=/tmp && rocprofv3 --pmc {c} -d <out>/{d} -o pmc --output-format csv -- python3 "
+           "<repo>/bench.py --no-cpu-baseline --no-probe --rows none --tau 0 --rho 0.9 --copy-calibration --steps 2 "
+           "--warmup 1 --dense-steps 1")
+    path = os.path.join(PROFILES, "attention_cfg4_topk0.9_counters.md")
+    with open(path, "w") as f:
+        f.write("# Short rows: top-k only, rho = 0.9 (107 of 1074 key blocks per row), 100-frame workload (cfg4)\n\n"
+                "Commands (the summary is written by `python -m paper_2509_07120_amd.profile_summary topk <out>/tcc <out>/pipes`):\n\n"
+                "    " + cmd.format(c="TCC_HIT_sum TCC_MISS_sum TCC_REQ_sum", d="tcc") + "\n"
+                "    " + cmd.format(c="SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES SQ_WAVE_CYCLES SQ_WAIT_ANY SQ_WAIT_INST_ANY "
+                                      "SQ_INSTS_MFMA SQ_ACTIVE_INST_VALU SQ_BUSY_CYCLES GRBM_GUI_ACTIVE", d="pipes") + "\n\n"
+                f"Kernel source hash (attn_bf16.hip, sha256/16): {source_sha()}.  Per dispatch of `attn_bf16_kernel` "
+                f"({n_sparse} sparse launches at rho = 0.9, then the dense launches of the same inputs):\n\n"
+                "| launch | ms | L2 requests | L2 hit rate | L2 misses x 128 B | clock GHz | MFMA pipe busy (of CU-busy time) | CUs busy (of the launch) | waves ready but not issued |\n"
+                "|---|---|---|---|---|---|---|---|---|\n")
+        for i, (t, m) in enumerate(zip(T, P)):
+            kind = "rho 0.9" if i < n_sparse else "dense"
+            clock = m["GRBM_GUI_ACTIVE"] / 8.0 / (m["ms"] * 1e-3) / 1e9
+            cu_busy = m["SQ_BUSY_CU_CYCLES"] / 256.0 / (m["ms"] * 1e-3 * clock * 1e9)
+            f.write(f"| {kind} {i} | {t['ms']:.2f} | {t['TCC_REQ_sum']:.4g} | {t['TCC_HIT_sum'] / t['TCC_REQ_sum']:.3f} | "
+                    f"{t['TCC_MISS_sum'] * 128 / 1e9:.1f} GB | {clock:.3f} | "
+                    f"{m['SQ_VALU_MFMA_BUSY_CYCLES'] / (4.0 * m['SQ_BUSY_CU_CYCLES']):.3f} | {cu_busy:.3f} | "
+                    f"{m['SQ_WAIT_INST_ANY'] / m['SQ_WAVE_CYCLES']:.3f} |\n")
+        f.write("""
+Reading.  With rows of 107 tiles the matrix pipes are as busy, while a CU is busy, as with rows of 966 tiles; what
+is lost is clock (the L2 misses are served by the Infinity Cache at several TB/s, and that traffic takes power from
+the core clock) and CU time (every row pays its start-up and end merge, and the launch ends with a partly filled
+round of workgroups).  The L2 hit rate is low because the generator's kept sets are nearly random subsets of the
+key blocks: the 64 workgroups of an XCD walk their lists in ascending order, but a block that six of them need is
+needed over a window of about +-50 tiles, many times what 4 MB of L2 hold.
+""")
+    print(open(path).read())
+
+
 def main(argv) -> int:
     if len(argv) >= 4 and argv[1] == "stats":
         cmd_stats(argv[2], argv[3])
@@ -282,6 +322,8 @@ def main(argv) -> int:
         cmd_traffic(argv[2], argv[3], argv[4])
     elif len(argv) >= 3 and argv[1] == "pipes":
         cmd_pipes(*argv[2:])
+    elif len(argv) >= 4 and argv[1] == "topk":
+        cmd_topk(argv[2], argv[3])
     else:
         print(__doc__)
         return 2

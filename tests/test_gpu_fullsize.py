@@ -69,6 +69,49 @@ def test_full_size_layer(B, cfg_id, tau, mask_heads, attn_heads, n_blocks):
     assert worst[2] <= BF16_MAX and worst[3] <= BF16_MEAN, worst
 
 
+def test_higher_resolution_layer(B):
+    """The higher-resolution shape (25 frames x 5481 tokens, the paper's discussion of larger inputs):
+    masks of two heads bit-exact, attention on sampled query blocks of two heads, plain and with the
+    special-token split (125 special tokens: one ragged special block; 136,900 patch tokens: 1069
+    full patch blocks and one of 68 tokens inside the sequence)."""
+    cfg = CONFIGS[6]
+    tau = 0.9
+    q, k, v = generate(cfg, heads=2)
+    tq, tk, tv = (to_device(x, cfg.dtype) for x in (q, k, v))
+    out, kv_idx, kv_cnt, bits = B.sparse_global_attention(tq, tk, tv, cfg.block, tau)
+    torch.cuda.synchronize()
+    nb = cfg.n_blocks
+    got_mask = bits_to_mask(bits, nb)
+    _, _, logits, probs, want_mask = oracle_mask_pipeline(q, k, cfg.block, tau, 1.0)
+    unexcused, excused = unexcused_mask_mismatches(got_mask, want_mask, logits, probs, tau, 1.0)
+    assert unexcused == 0, (unexcused, excused)
+    rng = np.random.default_rng(6)
+    cnt = kv_cnt.cpu().numpy()
+    for h in range(2):
+        blocks = _sample_blocks(cnt[h], nb, rng, 6)
+        want = O.sparse_attention(q[h:h + 1], k[h:h + 1], v[h:h + 1], got_mask[h:h + 1], cfg.block, q_blocks=blocks)
+        mx, mean = attn_errors(out[h:h + 1], want)
+        assert mx <= BF16_MAX and mean <= BF16_MEAN, (h, mx, mean)
+    # the same inputs with the split of Sec. 4.2, against the oracle's statement of that section
+    special = (np.arange(cfg.n_tokens) % cfg.tokens_per_frame) < 5
+    patch_idx, special_idx = np.flatnonzero(~special), np.flatnonzero(special)
+    plan = B.SpecialTokenPlan(torch.from_numpy(special), cfg.block, "cuda")
+    out_s, _, _, bits_s = B.sparse_global_attention_special(tq, tk, tv, plan, tau)
+    torch.cuda.synchronize()
+    npb = plan.n_patch_blocks
+    blocks = [0, 1, npb // 2, npb - 2, npb - 1]
+    want, want_pmask = O.special_token_attention(q, k, v, patch_idx, special_idx, cfg.block, tau, 1.0, patch_blocks=blocks)
+    sub = bits_to_mask(bits_s, plan.n_blocks)[:, :npb, :npb]
+    qp, kp = O.pool_blocks(q[:, patch_idx], cfg.block), O.pool_blocks(k[:, patch_idx], cfg.block)
+    lg = O.block_logits(qp, kp, 1.0 / 8.0)
+    unexcused, excused = unexcused_mask_mismatches(sub, want_pmask, lg, O.block_softmax(lg), tau, 1.0)
+    assert unexcused == 0, (unexcused, excused)
+    rows = np.concatenate([patch_idx[I * cfg.block:(I + 1) * cfg.block] for I in blocks] + [special_idx])
+    mx, mean = attn_errors(out_s[:, torch.from_numpy(rows).cuda()], want[:, rows])
+    print(f"cfg6 split: max={mx:.2e} mean={mean:.2e}")
+    assert mx <= BF16_MAX and mean <= BF16_MEAN, (mx, mean)
+
+
 def test_topk_only_selection_at_full_size(B):
     """tau = 0 with a top-k floor (the supplementary sweep of the benchmark): exactly floor(nb (1-rho)) blocks per row."""
     cfg = CONFIGS[4]
