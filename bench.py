@@ -336,8 +336,19 @@ def main() -> int:
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    w = Workload(B, torch, cfg)
+    H, N, d, b = w.H, w.N, w.d, w.b
+
+    # ---- headline: exactly --steps timed steps of the whole layer -------------------------------------
+    head, extra = w.row(args.tau, args.rho, args.steps, args.warmup, dense_steps=args.dense_steps)
+    print("[bench] attention ms per step: " + ", ".join(f"{x:.2f}" for x in extra["per_stage"]["attention"]), file=sys.stderr,
+          flush=True)
+    wall_ms, flops = extra["wall_ms"], extra["flops"]
+    attn_mean_ms = statistics.fmean(extra["per_stage"]["attention"])
+
     # ---- what the matrix pipes sustain on this machine with no memory traffic (the part clocks down with
-    # the switching activity of the operands; the attention kernel is to be read against these) -------
+    # the switching activity of the operands; the attention kernel is to be read against these).  After
+    # the headline, so that the headline is measured on a part in the state the driver hands over. ------
     probe = None
     if not args.no_probe:
         probe = {"what": "v_mfma_f32_32x32x16_bf16 only, registers only, 2 workgroups x 4 waves per CU; 'softmax' adds, "
@@ -352,15 +363,6 @@ def main() -> int:
                  "random_operands_softmax": B.bsga_probe_mfma(1, 2)}
         print("[bench] mfma probe: " + json.dumps({k: v for k, v in probe.items() if k not in ("what", "unit")}),
               file=sys.stderr, flush=True)
-    w = Workload(B, torch, cfg)
-    H, N, d, b = w.H, w.N, w.d, w.b
-
-    # ---- headline: exactly --steps timed steps of the whole layer -------------------------------------
-    head, extra = w.row(args.tau, args.rho, args.steps, args.warmup, dense_steps=args.dense_steps)
-    print("[bench] attention ms per step: " + ", ".join(f"{x:.2f}" for x in extra["per_stage"]["attention"]), file=sys.stderr,
-          flush=True)
-    wall_ms, flops = extra["wall_ms"], extra["flops"]
-    attn_mean_ms = statistics.fmean(extra["per_stage"]["attention"])
 
     rows = []
 
