@@ -472,51 +472,61 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   // after_reads() runs once every LDS read of the tile has been consumed.
   // ka, va, sc, w: working registers (the pipelined loop lends its own, which are free between runs).
   auto compute_tile = [&](auto safec, unsigned boff, int limit, auto&& after_reads, bf16x8 (&ka)[4],
-                          bf16x8 (&va)[2][2], f32x16& sc, u32x4 (&w)[2]) {
+                          bf16x8 (&va)[2][2], f32x16 (&sc)[2], u32x4 (&w)[2][2]) {
     constexpr bool SAFE = decltype(safec)::value;
     const bool ragged = limit < (kh + 1) * KW;
 #pragma unroll
     for (int u = 0; u < NH; ++u) {
       read_k(ka, boff, u);
       read_v(va, boff, u);
+      // the scores of both query halves first (eight MFMAs in a row), so that the weights of the
+      // first half are computed while the matrix pipe still works on the second, and the O update
+      // of the first half runs under the weights of the second
+      float base[2];
 #pragma unroll
       for (int b2 = 0; b2 < 2; ++b2) {
-        const float base = (SAFE && m_ref[b2] != -INFINITY) ? m_ref[b2] : 0.f;
+        base[b2] = (SAFE && m_ref[b2] != -INFINITY) ? m_ref[b2] : 0.f;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sc[i] = -base;
+        for (int i = 0; i < 16; ++i) sc[b2][i] = -base[b2];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c], qf[b2][c], sc, 0, 0, 0);
-        if (ragged) mask_keys(sc, u, limit);
+        for (int c = 0; c < 4; ++c) sc[b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[c], qf[b2][c], sc[b2], 0, 0, 0);
+      }
+      if (ragged) {
+        mask_keys(sc[0], u, limit);
+        mask_keys(sc[1], u, limit);
+      }
+#pragma unroll
+      for (int b2 = 0; b2 < 2; ++b2) {
         if constexpr (SAFE) {
           float tmax = -INFINITY;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sc[i]);
+          for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, sc[b2][i]);
           tmax = fmaxf(tmax, xor32(tmax));
           const bool unset = m_ref[b2] == -INFINITY;
           const bool raise = unset ? (tmax > -INFINITY) : (tmax > kRaise);
           if (__any(raise)) {  // rare after the first tile
             const float shift = raise ? tmax : 0.f;
             const float alpha = unset ? 1.f : exp2f(-shift);  // nothing accumulated yet while unset
-            if (raise) m_ref[b2] = base + shift;
+            if (raise) m_ref[b2] = base[b2] + shift;
             l_run[b2] *= alpha;
 #pragma unroll
             for (int db = 0; db < 2; ++db)
 #pragma unroll
               for (int i = 0; i < 16; ++i) o[db][b2][i] *= alpha;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) sc[i] -= shift;
+            for (int i = 0; i < 16; ++i) sc[b2][i] -= shift;
           }
         }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) weigh_pair(sc, w, l_run[b2], j);
+        for (int j = 0; j < 8; ++j) weigh_pair(sc[b2], w[b2], l_run[b2], j);
 #pragma unroll
         for (int db = 0; db < 2; ++db)
 #pragma unroll
           for (int cp = 0; cp < 2; ++cp)
-            o[db][b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db][cp], __builtin_bit_cast(bf16x8, w[cp]),
+            o[db][b2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db][cp], __builtin_bit_cast(bf16x8, w[b2][cp]),
                                                                 o[db][b2], 0, 0, 0);
-        if (u == NH - 1 && b2 == 0) after_reads();
       }
+      if (u == NH - 1) after_reads();
     }
   };
 
@@ -528,8 +538,8 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     issue(J_cur, Int<0>{});
     Tile J_pre = raw_at(1);  // list entries are fetched a tile before they are used
     bf16x8 ka[4], va[2][2];
-    f32x16 sc;
-    u32x4 w[2];
+    f32x16 sc[2];
+    u32x4 w[2][2];
     for (int it = 0; it < ntiles; ++it) {
       const int buf = it & 1;
       const Tile J_next = (it + 1 < ntiles) ? fix(J_pre, it + 1) : Tile{0, -1};
@@ -735,7 +745,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     // ---- from the first ragged tile on: plain tiles (the same buffers and the same one barrier per
     // tile; the loads stay two tiles ahead) ------------------------------------------------------------
     for (; T < ntiles; ++T) {
-      compute_tile(std::false_type{}, (T & 1) * TILE_BYTES, wave_limit(J_cur), []() {}, ka, va[0], sc[0], pw[0]);
+      compute_tile(std::false_type{}, (T & 1) * TILE_BYTES, wave_limit(J_cur), []() {}, ka, va[0], sc, pw);
       const Tile J2 = (T + 2 < ntiles) ? fix(J_pre, T + 2) : J_cur;
       J_pre = raw_at(T + 3);
       __builtin_amdgcn_s_waitcnt(0x0F70);  // this wave's share of tile T+1 has landed
