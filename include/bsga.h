@@ -146,9 +146,14 @@ size_t bsga_attn_workspace_bytes(int dtype, int heads, int64_t n_tokens, int hea
  *            contents are overwritten; calls sharing one workspace must be stream-ordered.  May be
  *            NULL: the query blocks are then launched in index order instead of heaviest first
  *            (same results, a longer tail when row lengths differ a lot).
- * bf16: products on bf16 MFMA with fp32 accumulation, fp32 online softmax.  softmax_scale > 0.
+ * bf16: products on bf16 MFMA with fp32 accumulation, fp32 softmax weights.  softmax_scale > 0.
  * The index lists are trusted to be in range (they come from bsga_select_blocks); block
  * indices are clamped to [0, nb) before use so a corrupt list cannot read out of bounds.
+ * Any order of a row's entries gives the same result up to rounding; the ascending order that
+ * bsga_select_blocks writes is the fast one (a ragged block, which is always the last block of the
+ * sequence or of its first part, should come last or nearly last in its row: the tiles after it
+ * take a slower path).  K and V must be finite everywhere: rows of a tile that are not keys of a
+ * listed block are multiplied by a weight of exactly zero, not skipped.
  */
 int bsga_sparse_attn(const void* q, const void* k, const void* v, int dtype, int heads,
                      int64_t n_tokens, int head_dim, int block, float softmax_scale,

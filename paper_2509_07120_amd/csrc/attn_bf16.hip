@@ -3,7 +3,9 @@
 // weights in the log2 domain.
 //
 // Work split.  One workgroup per (head, query block of B rows); it walks the row's kept key
-// blocks (tiles of B keys).  Waves are arranged WQ x 2: wave (qi, kh) owns 64 query rows (qi)
+// blocks (tiles of B keys; with key blocks of B/2 keys a tile is two consecutive list entries).
+// Blocks are those of a sequence cut in two separately blocked parts (Sec. 4.2; n_first = n_tokens
+// is the plain blocking).  Waves are arranged WQ x 2: wave (qi, kh) owns 64 query rows (qi)
 // and one half of every key tile (kh), so each K/V operand fetched from LDS into registers feeds
 // two MFMAs (register-file traffic, not LDS bandwidth, is what this saves: LDS read data and MFMA
 // operands share the VGPR ports).  The two key halves keep independent softmax states that are
@@ -27,9 +29,15 @@
 // the weights as exp2 of the raw scaled logits, i.e. with reference 0 for every row: any reference
 // gives the same O / l, the choice only matters for range, and the range is checked afterwards
 // (see pass()).  Only if that check fails is the workgroup repeated with a running reference
-// maximum (SAFE pass).  Row sums are taken from the fp32 weights; V is multiplied by their bf16
-// roundings, so numerator and denominator differ by at most one bf16 rounding (2^-9 relative),
-// the same size as rounding the output itself.
+// maximum (SAFE pass).  V is multiplied by the bf16 roundings of the weights.  The pipelined loop
+// sums those same bf16 weights (on the matrix pipe, see fast_loop), so numerator and denominator
+// agree exactly; the plain tile code sums the fp32 weights, which differ from the bf16 ones by at
+// most one rounding (2^-9 relative), the size of rounding the output itself.
+//
+// Tile rows that are not keys of the listed block (past the end of a ragged block, or the absent
+// second half of a tile of half-size key blocks) get weight exactly 0: their scores are set to -inf
+// before they are exponentiated.  Only the plain tile code masks; the pipelined loop runs over the
+// row's leading full tiles and hands the rest of the row to the plain code.
 #include <stdio.h>
 #include <stdlib.h>
 

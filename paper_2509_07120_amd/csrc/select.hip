@@ -216,16 +216,19 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
   if (!keep_all) {
     int n_gt, ties;
     double mass_gt;
-    T = find_threshold<E, true>(p, key_min, key_max, nb_ranked, tau, 0, n_gt, mass_gt, ties);
-    const double pt = __longlong_as_double(static_cast<long long>(T));
-    double run = mass_gt;
-    n_ties = 0;
-    do {
-      run += pt;
-      ++n_ties;
-    } while (run < tau && n_ties < ties);
-    const int n_cdf = n_gt + n_ties;
-    if (n_cdf < k_target) {  // the top-k floor decides
+    int n_cdf = 1;  // tau <= 0: the first ranked block already covers it (top-k only selection)
+    if (tau > 0.0) {
+      T = find_threshold<E, true>(p, key_min, key_max, nb_ranked, tau, 0, n_gt, mass_gt, ties);
+      const double pt = __longlong_as_double(static_cast<long long>(T));
+      double run = mass_gt;
+      n_ties = 0;
+      do {
+        run += pt;
+        ++n_ties;
+      } while (run < tau && n_ties < ties);
+      n_cdf = n_gt + n_ties;
+    }
+    if (n_cdf < k_target || !(tau > 0.0)) {  // the top-k floor decides
       T = find_threshold<E, false>(p, key_min, key_max, nb_ranked, tau, k_target, n_gt, mass_gt, ties);
       n_ties = k_target - n_gt;
     }
