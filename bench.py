@@ -314,6 +314,10 @@ def main() -> int:
                          "weights) dense and sparse; goes into the JSON")
     ap.add_argument("--asym", action="store_true",
                     help="also time the layer with query blocks of 128 and key blocks of 64; goes into the JSON")
+    ap.add_argument("--locality", action="store_true",
+                    help="also time the attention kernel on short rows (10 %% of the key blocks) whose lists are random per "
+                         "row / identical within a head / a band around the row: separates tile locality from per-row "
+                         "overhead; goes into the JSON")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run one 1 GiB device-to-device copy first (reference dispatch for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -403,6 +407,43 @@ def main() -> int:
             del blk, a
         del x
 
+    locality_rows = []
+    if args.locality:
+        import numpy as np
+        nbk = cfg.n_blocks
+        kc = max(1, nbk // 10)
+        rng = np.random.default_rng(0)
+        cnt_l = torch.full((H, nbk), kc, dtype=torch.int32, device="cuda")
+        dense_ms = w.time_dense(2)
+        for kind in ("random per row", "identical within a head", "band around the row"):
+            a = np.zeros((H, nbk, nbk), np.int32)
+            for h_ in range(H):
+                if kind == "identical within a head":
+                    a[h_, :, :kc] = np.sort(rng.choice(nbk - 1, kc, replace=False))
+                else:
+                    for I in range(nbk):
+                        if kind == "random per row":
+                            a[h_, I, :kc] = np.sort(rng.choice(nbk - 1, kc, replace=False))
+                        else:
+                            lo = min(max(I - kc // 2, 0), nbk - 1 - kc)
+                            a[h_, I, :kc] = np.arange(lo, lo + kc)
+            idx_l = torch.from_numpy(a).cuda()
+            ts = []
+            for _ in range(args.row_steps + 1):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                B.bsga_sparse_attn(w.q, w.k, w.v, b, idx_l, cnt_l, out=w.out, workspace=w.ws)
+                e1.record()
+                torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1))
+            ms = statistics.median(ts[1:])
+            fl = kept_flops(idx_l, cnt_l, N, b)
+            row = {"lists": kind, "blocks_per_row": kc, "attention_ms": ms, "kept_tflops_attention": fl / (ms * 1e-3) / 1e12,
+                   "dense_tflops": 4.0 * H * float(N) * float(N) * d / (dense_ms * 1e-3) / 1e12}
+            locality_rows.append(row)
+            print("[locality] " + json.dumps(row), file=sys.stderr, flush=True)
+            del idx_l
+
     asym_rows = []
     if args.asym and b == 128:
         nbk64 = -(-N // 64)
@@ -491,6 +532,8 @@ def main() -> int:
         rec["mfma_probe"] = probe
     if rows:
         rec["rows"] = rows
+    if locality_rows:
+        rec["short_row_locality"] = locality_rows
     if asym_rows:
         rec["query128_key64_blocks"] = asym_rows
     if block_rows:
