@@ -114,8 +114,9 @@ __device__ __forceinline__ i32x4 make_rsrc(const void* base, unsigned bytes) {
 // equal length would only break that up.  Counting sort by kOrderClasses classes of kept count /
 // nb; the classes whose lower bound is below 1.4 x the mean count are merged into one.  Four small
 // kernels: per-head class histogram -> merge -> exclusive scan of the [class][head] table ->
-// placement.  Rows of one (class, head) group come out in arbitrary order, which only changes which
-// workgroup computes which row.
+// placement.  The rows of the merged class keep their natural order inside a head (neighbouring
+// query blocks tend to keep similar key blocks); rows of one of the longer (class, head) groups come
+// out in arbitrary order, which only changes which workgroup computes which row.
 constexpr int kOrderClasses = 32;
 
 __device__ __forceinline__ int order_class(int cnt, int nb) {  // class 0 holds the longest rows
@@ -201,14 +202,31 @@ __global__ __launch_bounds__(256) void order_place_kernel(const int32_t* __restr
                                                           int heads, const int32_t* __restrict__ table,
                                                           int32_t* __restrict__ order) {
   __shared__ int next[kOrderClasses];
+  __shared__ int wave_bulk[4];
   const int h = blockIdx.x;
   const int t = threadIdx.x;
   if (t < kOrderClasses) next[t] = table[int64_t(t) * heads + h];
   const int c_bulk = table[int64_t(kOrderClasses) * heads];
   __syncthreads();
-  for (int I = t; I < nb; I += 256) {
-    const int pos = atomicAdd(&next[min(order_class(kv_cnt[int64_t(h) * nb + I], nbk), c_bulk)], 1);
-    order[pos] = h * nb + I;
+  int bulk_next = next[c_bulk];  // every thread keeps its own copy of the bulk group's fill position
+  for (int base = 0; base < nb; base += 256) {
+    const int I = base + t;
+    const int cls = I < nb ? min(order_class(kv_cnt[int64_t(h) * nb + I], nbk), c_bulk) : -1;
+    // the bulk group keeps the natural order of its rows: rank of this row among the chunk's bulk rows
+    const bool bulk = cls == c_bulk;
+    const unsigned long long vote = __ballot(bulk);
+    const int below = __popcll(vote & ((1ull << (t & 63)) - 1ull));
+    if ((t & 63) == 0) wave_bulk[t >> 6] = __popcll(vote);
+    __syncthreads();
+    int before = 0, chunk = 0;
+    for (int w = 0; w < 4; ++w) {
+      before += w < (t >> 6) ? wave_bulk[w] : 0;
+      chunk += wave_bulk[w];
+    }
+    if (bulk) order[bulk_next + before + below] = h * nb + I;
+    else if (cls >= 0) order[atomicAdd(&next[cls], 1)] = h * nb + I;
+    bulk_next += chunk;
+    __syncthreads();
   }
 }
 
@@ -253,8 +271,15 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   const int qi = wave % WQ;
   const int kh = wave / WQ;
   int h = blockIdx.y, I = blockIdx.x;
-  if (order != nullptr) {  // row number blockIdx.y * gridDim.x + blockIdx.x of the launch order
-    const int row = __builtin_amdgcn_readfirstlane(order[int64_t(blockIdx.y) * nb + blockIdx.x]);
+  if (order != nullptr) {
+    // Workgroup number w of the grid runs on XCD w % 8, and the chip holds 512 workgroups at a time,
+    // 64 per XCD.  Inside each full group of 512 consecutive workgroups the positions of the launch
+    // order are dealt out so that an XCD gets 64 consecutive ones: rows that are neighbours in the
+    // order, whose lists tend to overlap, then share one L2 instead of being spread over all eight.
+    const int64_t w = int64_t(blockIdx.y) * nb + blockIdx.x, total = int64_t(gridDim.y) * nb;
+    const int r = static_cast<int>(w & 511);
+    const int64_t pos = (w - r) + 512 <= total ? (w - r) + (r & 7) * 64 + (r >> 3) : w;
+    const int row = __builtin_amdgcn_readfirstlane(order[pos]);
     h = min(max(row / nb, 0), static_cast<int>(gridDim.y) - 1);
     I = min(max(row % nb, 0), nb - 1);
   }
