@@ -13,7 +13,9 @@
  *   - All tensor pointers are DEVICE pointers unless marked "host".  The caller owns
  *     every buffer; the library allocates, frees and copies nothing, and only enqueues
  *     work on `stream` (a hipStream_t passed as void*; NULL = the null stream).  Calls
- *     return after enqueueing; they do not synchronise.
+ *     return after enqueueing; they do not synchronise.  They record kernel launches only
+ *     (no memset, copy or allocation), so they may be called on a stream that is being
+ *     captured into a HIP graph (bsga_sparse_attn_noalloc: after one call outside a capture).
  *   - Tensors are contiguous row-major; Q, K, V, O are [heads, n_tokens, head_dim]
  *     (a batch dimension is folded into heads).  Pointers must be 16-byte aligned.
  *   - head_dim must be 64.  block must be 64 or 128.  dtype: BSGA_BF16 or BSGA_FP32
