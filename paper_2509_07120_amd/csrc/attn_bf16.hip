@@ -243,6 +243,7 @@ struct Segments {
 // the second half is empty).
 struct Tile {
   int a, b;
+  unsigned oa, ob;  // byte offsets of the blocks' first keys inside the head (filled in by fix())
 };
 
 // B: query rows per workgroup = keys per LDS tile.  KB: size of the key blocks the index list refers
@@ -378,22 +379,38 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   typedef const int32_t __attribute__((address_space(4))) * const_idx_ptr;
   const const_idx_ptr cidx = (const_idx_ptr)my_idx;
   auto raw_at = [&](int it) -> Tile {
-    if (dense) return Tile{min(it, nbk - 1), -1};
+    if (dense) return Tile{min(it, nbk - 1), -1, 0u, 0u};
     constexpr int PER = HALF ? 2 : 1;  // list entries per tile
     const int e = min(it, ntiles - 1) * PER;
-    Tile t{cidx[e], -1};
+    Tile t{cidx[e], -1, 0u, 0u};
     if constexpr (HALF) t.b = cidx[min(e + 1, count - 1)];
     return t;
   };
+  // An absent second half gets an offset past the end of the head's buffer: the bounds check of
+  // the loads then zero-fills it.
   auto fix = [&](const Tile& r, int it) -> Tile {  // r = raw_at(it)
-    if (dense) return r;
-    Tile t{min(max(r.a, 0), nbk - 1), -1};
+    Tile t{r.a, -1, 0u, head_size};
+    if (!dense) {
+      t.a = min(max(r.a, 0), nbk - 1);
+      if constexpr (HALF) {
+        if (min(it, ntiles - 1) * 2 + 1 < count) t.b = min(max(r.b, 0), nbk - 1);
+      }
+    }
+    t.oa = static_cast<unsigned>(key_start(t.a)) * 128u;
     if constexpr (HALF) {
-      if (min(it, ntiles - 1) * 2 + 1 < count) t.b = min(max(r.b, 0), nbk - 1);
+      if (t.b >= 0) t.ob = static_cast<unsigned>(key_start(t.b)) * 128u;
     }
     return t;
   };
   auto block_at = [&](int it) -> Tile { return fix(raw_at(it), it); };
+  // The offsets are operands of scalar type in the load instructions.  A tile description that has
+  // been carried around a loop may live in vector registers (the same value in every lane): this
+  // moves the offsets back.
+  auto scalar = [&](Tile t) -> Tile {
+    t.oa = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(t.oa)));
+    t.ob = static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(t.ob)));
+    return t;
+  };
   // This wave's keys of a tile are the tile rows [kh*KW, (kh+1)*KW).  wave_limit(t) is the first of
   // them that is not a key of the listed block (a ragged block, or an absent second half): rows at
   // or past it hold zeros or tokens of another block, and their scores are masked before they are
@@ -429,8 +446,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   // the hardware bounds check, which makes the load write zeros for them (so V rows past the end
   // are finite; rows past a ragged block inside the sequence hold the following tokens).
   // With half-tile key blocks, loads i = 0, 1 fill tile rows 0..63 from block a and i = 2, 3 rows
-  // 64..127 from block b; an absent b gets an offset past the end of the buffer, so the bounds check
-  // zero-fills that half.
+  // 64..127 from block b (an absent b: zero-filled, see fix()).
   const unsigned dma_base = smem_addr + wave * 1024;  // this wave's 1 KB slice of every 4 KB (8 KB) group
   auto issue_part = [&](const Tile& J, auto bufc, auto i2c) {
     constexpr int buf = decltype(bufc)::value, i2 = decltype(i2c)::value;
@@ -438,15 +454,14 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     constexpr bool is_v = (i2 & 1) != 0;
     constexpr unsigned dst = NW * i * 1024 + (is_v ? V_BASE : 0) + buf * TILE_BYTES;
     if constexpr (HALF) {
-      const int Jx = (i >> 1) ? J.b : J.a;
-      const unsigned soff = Jx < 0 ? head_size : static_cast<unsigned>(key_start(Jx)) * 128u;
+      const unsigned soff = (i >> 1) ? J.ob : J.oa;
       if (is_v) {
-        dma16<dst>(vrsrc, voff, soff + (Jx < 0 ? 0u : (i & 1) * NW * 1024), dma_base);
+        dma16<dst>(vrsrc, voff, soff + (i & 1) * NW * 1024, dma_base);
       } else {
         dma16<dst>(krsrc, koff[i % KN], soff, dma_base);
       }
     } else {
-      const unsigned soff = static_cast<unsigned>(key_start(J.a)) * 128u;
+      const unsigned soff = J.oa;
       if (is_v) {
         dma16<dst>(vrsrc, voff, soff + i * NW * 1024, dma_base);
       } else {
@@ -575,10 +590,10 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     u32x4 w[2][2];
     for (int it = 0; it < ntiles; ++it) {
       const int buf = it & 1;
-      const Tile J_next = (it + 1 < ntiles) ? fix(J_pre, it + 1) : Tile{0, -1};
+      const Tile J_next = (it + 1 < ntiles) ? fix(J_pre, it + 1) : Tile{0, -1, 0u, 0u};
       __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of tile `it` has landed
       __syncthreads();                     // ... and so has everyone else's; buffer buf^1 is free
-      if (it + 1 < ntiles) issue_rt(J_next, buf ^ 1);
+      if (it + 1 < ntiles) issue_rt(scalar(J_next), buf ^ 1);
       // The list entries of the tile after next.  Scalar loads return out of order with LDS reads, so
       // a wait for LDS data would also wait for them: they are issued where every LDS read of the
       // tile has been consumed, and used at the top of the next tile.
@@ -754,7 +769,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
       // buffer pair 0, odd ones in pair 1)
       auto step = [&](auto bufc) {
         // the tile after next; at the end of the list one more (harmless) load of a valid tile
-        const Tile J2 = (T + 2 < ntiles) ? fix(J_pre, T + 2) : J_cur;
+        const Tile J2 = scalar((T + 2 < ntiles) ? fix(J_pre, T + 2) : J_cur);
         J_pre = raw_at(T + 3);
         tile(J2, bufc);
         J_cur = J_nxt;
@@ -779,7 +794,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     // tile; the loads stay two tiles ahead) ------------------------------------------------------------
     for (; T < ntiles; ++T) {
       compute_tile(std::false_type{}, (T & 1) * TILE_BYTES, wave_limit(J_cur), []() {}, ka, va[0], sc, pw);
-      const Tile J2 = (T + 2 < ntiles) ? fix(J_pre, T + 2) : J_cur;
+      const Tile J2 = scalar((T + 2 < ntiles) ? fix(J_pre, T + 2) : J_cur);
       J_pre = raw_at(T + 3);
       __builtin_amdgcn_s_waitcnt(0x0F70);  // this wave's share of tile T+1 has landed
       __syncthreads();                     // ... everyone's has, and nobody still reads tile T
