@@ -127,10 +127,11 @@ int bsga_gather_tokens(const void* src, int dtype, int heads, int64_t n_src, int
                        const int32_t* index, int64_t n_dst, void* dst, void* stream);
 
 /*
- * Bytes of device workspace bsga_sparse_attn needs for this shape (bsga_dense_attn needs none and
- * accepts NULL).  Q, K and V are read in place and all intermediates stay on chip; the workspace
- * holds the launch order of the (head, query block) rows, heaviest first (4 bytes per row, sized for
- * block 64 and a split sequence, plus 128 bytes per head and 16 bytes; 0 for fp32 and for invalid
+ * Bytes of device workspace bsga_sparse_attn needs for this shape (bsga_dense_attn uses 16 bytes
+ * of one and accepts NULL).  Q, K and V are read in place and all intermediates stay on chip; the
+ * workspace holds the launch order of the (head, query block) rows, heaviest first, and the counter
+ * through which the last rows of a large launch are handed out at run time (4 bytes per row, sized
+ * for block 64 and a split sequence, plus 128 bytes per head and 16 bytes; 0 for fp32 and for invalid
  * arguments).
  */
 size_t bsga_attn_workspace_bytes(int dtype, int heads, int64_t n_tokens, int head_dim);
@@ -146,8 +147,10 @@ size_t bsga_attn_workspace_bytes(int dtype, int heads, int64_t n_tokens, int hea
  *   lse      nullable [heads, n_tokens] float32: natural-log sum-exp of each row's kept logits
  *   workspace, workspace_bytes: device scratch of at least bsga_attn_workspace_bytes(...) bytes;
  *            contents are overwritten; calls sharing one workspace must be stream-ordered.  May be
- *            NULL: the query blocks are then launched in index order instead of heaviest first
- *            (same results, a longer tail when row lengths differ a lot).
+ *            NULL: the query blocks are then launched in index order instead of heaviest first,
+ *            and every row is tied to the workgroup of its number (same results; a longer tail when
+ *            row lengths differ a lot, and a few per cent slower on large shapes because the XCDs of
+ *            a part do not run equally fast and cannot then share the last rows unevenly).
  * bf16: products on bf16 MFMA with fp32 accumulation, fp32 softmax weights.  softmax_scale > 0.
  * The index lists are trusted to be in range (they come from bsga_select_blocks); block
  * indices are clamped to [0, nb) before use so a corrupt list cannot read out of bounds.
@@ -215,7 +218,9 @@ int bsga_sparse_attn_split(const void* q, const void* k, const void* v, int dtyp
 
 /*
  * Dense attention baseline  (Sec. 4.1, Eq. (1)): softmax(softmax_scale * Q K^T) V per head.
- * Same tensors, workspace and numerics as bsga_sparse_attn, every key visible.
+ * Same tensors and numerics as bsga_sparse_attn, every key visible.  workspace: NULL, or at least
+ * 16 bytes (16-byte aligned; a smaller or misaligned one is ignored) for the counter that hands out
+ * the last rows of a large launch at run time; overwritten; stream-ordered like the others.
  */
 int bsga_dense_attn(const void* q, const void* k, const void* v, int dtype, int heads,
                     int64_t n_tokens, int head_dim, float softmax_scale, void* out, float* lse,

@@ -323,8 +323,11 @@ def bsga_sparse_attn_split(q, k, v, block: int, n_first: int, kv_idx: torch.Tens
 
 
 def bsga_dense_attn(q, k, v, softmax_scale: Optional[float] = None, return_lse: bool = False,
-                    out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
-    """Dense softmax attention baseline; returns O (and lse)."""
+                    out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                    balanced: bool = True):
+    """Dense softmax attention baseline; returns O (and lse).
+    balanced = False passes no workspace: every row is then computed by the workgroup of its number
+    instead of the last rows being handed out at run time."""
     _require(q, "q"); _require(k, "k", q.dtype); _require(v, "v", q.dtype)
     H, N, d = q.shape
     if softmax_scale is None:
@@ -332,7 +335,7 @@ def bsga_dense_attn(q, k, v, softmax_scale: Optional[float] = None, return_lse: 
     if out is None:
         out = torch.empty_like(q)
     lse = torch.empty((H, N), dtype=torch.float32, device=q.device) if return_lse else None
-    workspace, ws_bytes = _workspace(q, workspace)
+    workspace, ws_bytes = _workspace(q, workspace) if balanced else (None, 0)
     _check(lib.bsga_dense_attn(_ptr(q), _ptr(k), _ptr(v), _dtype_code(q), H, N, d, float(softmax_scale),
                                _ptr(out), _ptr(lse), _ptr(workspace), ws_bytes, _stream(q)))
     return (out, lse) if return_lse else out

@@ -10,6 +10,8 @@
 // two MFMAs (register-file traffic, not LDS bandwidth, is what this saves: LDS read data and MFMA
 // operands share the VGPR ports).  The two key halves keep independent softmax states that are
 // merged once at the end.  Two workgroups share a CU (two waves per SIMD).
+// Which workgroup computes which row: see the top of the kernel (launch order, 64 consecutive rows
+// per XCD, the last eighth of a large launch handed out at run time).
 //
 // Data movement.  K and V tiles go HBM/L2 -> LDS with direct-to-LDS loads (16 bytes per lane, no
 // staging registers), double buffered, with one workgroup barrier per tile.  Tiles stay row-major
@@ -159,6 +161,7 @@ __global__ __launch_bounds__(256) void order_merge_kernel(int32_t* __restrict__ 
     while (c < kOrderClasses - 1 && static_cast<double>(kOrderClasses - 1 - c) / (kOrderClasses - 1) >= 1.4 * mean) ++c;
     c_bulk = c;
     table[int64_t(kOrderClasses) * heads] = c;
+    table[int64_t(kOrderClasses) * heads + 1] = 0;  // the attention kernel's counter of rows handed out at run time
   }
   __syncthreads();
   const int cb = c_bulk;
@@ -230,6 +233,10 @@ __global__ __launch_bounds__(256) void order_place_kernel(const int32_t* __restr
   }
 }
 
+__global__ void zero_word_kernel(int* __restrict__ word) {
+  if (threadIdx.x == 0) *word = 0;
+}
+
 // Token blocks.  The sequence is two segments, tokens [0, n_first) and [n_first, n_tokens), each cut
 // into blocks of its own (Sec. 4.2 keeps the patch tokens and the special tokens in separate blocks);
 // nbq1 / nbk1 = number of query / key blocks of the first segment.  n_first = n_tokens is the plain
@@ -253,7 +260,7 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
     const unsigned char* __restrict__ q, const unsigned char* __restrict__ k, const unsigned char* __restrict__ v,
     unsigned short* __restrict__ out, float* __restrict__ lse, const int32_t* __restrict__ kv_idx,
     const int32_t* __restrict__ kv_cnt, const int32_t* __restrict__ order, int idx_stride, int64_t n_tokens, int nb,
-    int nbk, float scale_log2, Segments seg) {
+    int nbk, float scale_log2, Segments seg, int heads, int64_t n_static, int* __restrict__ next_row) {
   static_assert(KB == B || (2 * KB == B && B == 128), "key blocks are whole tiles or half tiles of 128");
   constexpr bool HALF = KB != B;          // two listed key blocks per tile
   constexpr int WQ = B / 64;              // waves along queries (64 rows each)
@@ -271,19 +278,34 @@ __global__ __launch_bounds__(2 * B, 2) void attn_bf16_kernel(
   const int g = lane >> 5;
   const int qi = wave % WQ;
   const int kh = wave / WQ;
-  int h = blockIdx.y, I = blockIdx.x;
-  if (order != nullptr) {
-    // Workgroup number w of the grid runs on XCD w % 8, and the chip holds 512 workgroups at a time,
-    // 64 per XCD.  Inside each full group of 512 consecutive workgroups the positions of the launch
-    // order are dealt out so that an XCD gets 64 consecutive ones: rows that are neighbours in the
-    // order, whose lists tend to overlap, then share one L2 instead of being spread over all eight.
-    const int64_t w = int64_t(blockIdx.y) * nb + blockIdx.x, total = int64_t(gridDim.y) * nb;
+  // Which (head, query block) row this workgroup computes.  Workgroup number w of the grid runs on
+  // XCD w % 8, whatever the XCDs' speeds, and the chip holds 512 workgroups at a time, 64 per XCD.
+  //  - The first n_static workgroups take positions of the launch order by their number.  Inside each
+  //    full group of 512 consecutive workgroups the positions are dealt out so that an XCD gets 64
+  //    consecutive ones: rows that are neighbours in the order, whose lists tend to overlap, then
+  //    share one L2 instead of being spread over all eight.
+  //  - The other workgroups (there are more of them than rows left) take the remaining positions
+  //    first come, first served, through one atomic counter, and leave at once when none is left.
+  //    Under load the XCDs of a part run at clocks that differ by several per cent; an XCD that is
+  //    through with its static share early thus takes more of the remaining rows than a slow one.
+  const int64_t total = int64_t(heads) * nb;
+  const int64_t w = int64_t(blockIdx.y) * nb + blockIdx.x;
+  int64_t pos;
+  if (w < n_static) {
     const int r = static_cast<int>(w & 511);
-    const int64_t pos = (w - r) + 512 <= total ? (w - r) + (r & 7) * 64 + (r >> 3) : w;
-    const int row = __builtin_amdgcn_readfirstlane(order[pos]);
-    h = min(max(row / nb, 0), static_cast<int>(gridDim.y) - 1);
-    I = min(max(row % nb, 0), nb - 1);
+    pos = (w - r) + 512 <= n_static ? (w - r) + (r & 7) * 64 + (r >> 3) : w;
+  } else {
+    int* slot = reinterpret_cast<int*>(smem);
+    if (tid == 0) *slot = atomicAdd(next_row, 1);
+    __syncthreads();
+    const int t = __builtin_amdgcn_readfirstlane(*slot);
+    __syncthreads();  // the slot lies where the first K tile goes
+    if (t >= total - n_static) return;  // the whole workgroup leaves, before any other barrier
+    pos = n_static + t;
   }
+  const int64_t row = order != nullptr ? int64_t(__builtin_amdgcn_readfirstlane(order[pos])) : pos;
+  const int h = static_cast<int>(min(max(row / nb, int64_t(0)), int64_t(heads - 1)));
+  const int I = static_cast<int>(min(max(row - int64_t(h) * nb, int64_t(0)), int64_t(nb - 1)));
   const int64_t head_bytes = int64_t(h) * n_tokens * 128;
   const int64_t rowid = int64_t(h) * nb + I;
   // this query block: first token and number of tokens (a block never crosses the segment boundary)
@@ -919,11 +941,30 @@ int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int
   const Segments seg = {static_cast<int>(n_first), static_cast<int>(ceil_div(n_first, block)),
                         static_cast<int>(ceil_div(n_first, block_k))};
   const int32_t* order = nullptr;
-  // ordering matters only when the grid does not fit the chip at once
-  if (kv_idx != nullptr && workspace != nullptr && int64_t(heads) * nb >= 1024 && int64_t(heads) * nb < (int64_t(1) << 30)) {
-    // workspace: [heads * nb] launch order, then the [classes][heads] table and one more word
+  const int64_t rows = int64_t(heads) * nb;
+  int64_t n_static = rows;  // without a workspace every row is taken by workgroup number
+  int extra = 0;                          // workgroups beyond one per row
+  int* next_row = nullptr;
+  // ordering and balancing matter only when the grid does not fit the chip at once
+  const bool big = workspace != nullptr && rows >= 1024 && rows < (int64_t(1) << 30);
+  if (big) {
+    // The last eighth of the rows is handed out at run time; half as many workgroups again as that
+    // are launched for it, so that an XCD can take up to 1.5 times its even share of those rows.
+    const int64_t dynamic = rows / 8;
+    n_static = (rows - dynamic) / 512 * 512;
+    extra = static_cast<int>((rows - n_static) / 2 + 512);
+  }
+  if (big && kv_idx == nullptr) {
+    // dense: the workspace holds the counter only
+    next_row = static_cast<int*>(workspace);
+    hipLaunchKernelGGL(zero_word_kernel, dim3(1), dim3(64), 0, stream, next_row);
+  }
+  if (big && kv_idx != nullptr) {
+    // workspace: [heads * nb] launch order, then the [classes][heads] table, the number of the merged
+    // class and the counter of the rows handed out at run time (cleared by order_merge_kernel)
     int32_t* ord = static_cast<int32_t*>(workspace);
     int32_t* table = ord + int64_t(heads) * nb;
+    next_row = table + int64_t(kOrderClasses) * heads + 1;
     hipLaunchKernelGGL(order_hist_kernel, dim3(heads), dim3(256), 0, stream, kv_cnt, nb, nbk, heads, table);
     hipLaunchKernelGGL(order_merge_kernel, dim3(1), dim3(256), 0, stream, table, heads);
     hipLaunchKernelGGL(order_scan_kernel, dim3(1), dim3(1024), 0, stream, table, int64_t(kOrderClasses) * heads);
@@ -932,7 +973,7 @@ int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int
     order = ord;
   }
   const float scale_log2 = softmax_scale * kLog2e;
-  dim3 grid(nb, heads);
+  dim3 grid(nb, heads + static_cast<int>(ceil_div(extra, nb)));
   const unsigned char* qp = static_cast<const unsigned char*>(q);
   const unsigned char* kp = static_cast<const unsigned char*>(k);
   const unsigned char* vp = static_cast<const unsigned char*>(v);
@@ -948,13 +989,13 @@ int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int
   }
   if (block == 64) {
     hipLaunchKernelGGL((attn_bf16_kernel<64, 64>), grid, dim3(128), lds64, stream, qp, kp, vp, op, lse, kv_idx,
-                       kv_cnt, order, idx_stride, n_tokens, nb, nbk, scale_log2, seg);
+                       kv_cnt, order, idx_stride, n_tokens, nb, nbk, scale_log2, seg, heads, n_static, next_row);
   } else if (block_k == 128) {
     hipLaunchKernelGGL((attn_bf16_kernel<128, 128>), grid, dim3(256), lds128, stream, qp, kp, vp, op, lse, kv_idx,
-                       kv_cnt, order, idx_stride, n_tokens, nb, nbk, scale_log2, seg);
+                       kv_cnt, order, idx_stride, n_tokens, nb, nbk, scale_log2, seg, heads, n_static, next_row);
   } else {
     hipLaunchKernelGGL((attn_bf16_kernel<128, 64>), grid, dim3(256), lds128, stream, qp, kp, vp, op, lse, kv_idx,
-                       kv_cnt, order, idx_stride, n_tokens, nb, nbk, scale_log2, seg);
+                       kv_cnt, order, idx_stride, n_tokens, nb, nbk, scale_log2, seg, heads, n_static, next_row);
   }
   return check_hip(hipGetLastError(), "bsga bf16 attention launch");
 }

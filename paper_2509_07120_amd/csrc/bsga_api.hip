@@ -96,6 +96,8 @@ static int attn_common(const char* fn, const void* q, const void* k, const void*
       return fail(BSGA_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", fn, workspace_bytes, need);
     if (!aligned16(workspace)) return fail(BSGA_ERR_INVALID_ARG, "%s: workspace must be 16-byte aligned", fn);
   }
+  // the dense kernel uses a workspace, if it gets one, for one counter (balancing rows across the XCDs)
+  if (!kv_idx && workspace && (workspace_bytes < 16 || !aligned16(workspace))) workspace = nullptr;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (dtype == BSGA_BF16)
     return launch_attn_bf16(q, k, v, heads, n_tokens, n_first, block, block_k, softmax_scale, kv_idx, kv_cnt, idx_stride, out, lse,

@@ -328,3 +328,23 @@ def test_launch_order_does_not_change_results(B):
     want = O.sparse_attention(q, k, v, mask, b, q_blocks=[0, 1, 17, nb - 1], heads=[0, 7])
     want[:, 5 * b:6 * b] = np.nan
     assert bf16_bars_ok(a, want)[0], bf16_bars_ok(a, want)
+
+
+def test_rows_handed_out_at_run_time_do_not_change_results(B):
+    """With a workspace, the last eighth of the rows of a large launch is not tied to workgroup
+    numbers: workgroups take those rows through a counter (an XCD that runs faster takes more).
+    Which workgroup computes a row must not matter: dense attention with and without the workspace
+    is bitwise the same, call after call (the counter is cleared by every call), and so is the
+    block-sparse kernel on a keep-all list."""
+    H, N, b = 10, 128 * 128 + 77, 128             # 1290 rows: above the 1024 that switch the hand-out on
+    q, k, v = _rand_qkv(H, N, 78, "bf16")
+    tq, tk, tv = (to_device(x, "bf16") for x in (q, k, v))
+    plain = B.bsga_dense_attn(tq, tk, tv, balanced=False)
+    for _ in range(3):
+        assert torch.equal(B.bsga_dense_attn(tq, tk, tv), plain)
+    nb = O.num_blocks(N, b)
+    idx, cnt = _lists(np.ones((H, nb, nb), dtype=bool))
+    for _ in range(2):
+        assert torch.equal(B.bsga_sparse_attn(tq, tk, tv, b, idx, cnt), plain)
+    want = O.sparse_attention(q, k, v, np.ones((H, nb, nb), dtype=bool), b, q_blocks=[0, nb - 2, nb - 1], heads=[0, 9])
+    assert bf16_bars_ok(plain, want)[0], bf16_bars_ok(plain, want)
