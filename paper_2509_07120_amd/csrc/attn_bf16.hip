@@ -946,7 +946,9 @@ int launch_attn_bf16(const void* q, const void* k, const void* v, int heads, int
   int extra = 0;                          // workgroups beyond one per row
   int* next_row = nullptr;
   // ordering and balancing matter only when the grid does not fit the chip at once
-  const bool big = workspace != nullptr && rows >= 1024 && rows < (int64_t(1) << 30);
+  // (and only while the extra workgroups fit the grid's second dimension)
+  const bool big = workspace != nullptr && rows >= 1024 && rows < (int64_t(1) << 30) &&
+                   heads + ceil_div(rows / 16 + 1024, nb) <= 65535;
   if (big) {
     // The last eighth of the rows is handed out at run time; half as many workgroups again as that
     // are launched for it, so that an XCD can take up to 1.5 times its even share of those rows.
